@@ -1,0 +1,179 @@
+/*
+ * dynamicrad.h -- C ABI of the DynamicRad attention hot path for AMD MI355X (gfx950).
+ *
+ * Three stages, each one call (paper: "Two-Mode Intra-Candidate Selection",
+ * Algorithm 1, and the masked attention of Eq. 13):
+ *
+ *   dr_block_scores     pooled Q/K proxy score per (query block, key block)
+ *   dr_build_mask       radial candidate geometry + per-row selection -> CSR
+ *   dr_sparse_attn_fwd  softmax attention restricted to the kept key blocks
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     never frees or reallocates them and keeps no reference after the call's
+ *     work on the stream has finished.
+ *   - Q, K, V, O are [B, H, N, d] with the innermost d contiguous; the three
+ *     outer strides are given in elements and are the same for all four.
+ *     Rows must be 16-byte aligned (base pointer and every stride * element
+ *     size a multiple of 16).
+ *   - Tokens are ordered frame-major: token p sits in frame p / (Hg*Wg) at
+ *     in-frame index p % (Hg*Wg) (row-major over the Hg x Wg grid).
+ *     N must equal Nf*Hg*Wg.  Blocks of Bs tokens are cut on the global token
+ *     index; the last block may be partial (Sb = ceil(N / Bs)).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without a host synchronisation,
+ *     except where a call says otherwise (first use of a new geometry).
+ *   - Every call returns a dr_status; nothing is thrown across the boundary.
+ *     dr_last_error(ctx) returns the text of the last failure on that context.
+ *     Argument errors are detected on the host before anything is launched.
+ *   - A dr_ctx owns device scratch and caches; it is bound to one device and
+ *     must not be used from two threads at once.  Two calls on different
+ *     streams that share one ctx race on its scratch.
+ */
+#ifndef DYNAMICRAD_H_
+#define DYNAMICRAD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dr_ctx dr_ctx;
+
+typedef enum {
+    DR_OK = 0,
+    DR_ERR_INVALID_ARG = 1,   /* null pointer, inconsistent shape, parameter out of range */
+    DR_ERR_UNSUPPORTED = 2,   /* valid request outside what the kernels cover (d, Bs, frame count) */
+    DR_ERR_CAPACITY = 3,      /* a caller-provided capacity is too small to even start */
+    DR_ERR_HIP = 4,           /* a HIP runtime call failed; text in dr_last_error */
+    DR_ERR_NOMEM = 5          /* scratch allocation failed */
+} dr_status;
+
+typedef enum { DR_F32 = 0, DR_BF16 = 1 } dr_dtype;
+
+typedef enum {
+    DR_MODE_STATIC_RATIO = 0,      /* keep the top max(1, floor(n*rho)) selectable blocks of a row by score */
+    DR_MODE_DYNAMIC_THRESHOLD = 1  /* keep the shortest score-descending prefix holding >= tau of the softmax mass */
+} dr_mode;
+
+/* Problem shape.  Paper notation: Nf frames, Nt = Hg*Wg tokens per frame, S = N tokens, Bs block size. */
+typedef struct {
+    int32_t B, H, N, d;            /* batch, heads, tokens, head dim (64 or 128) */
+    int32_t Nf, Hg, Wg, Bs;        /* frames, grid rows, grid cols, block size (32, 64 or 128) */
+    int32_t dtype;                 /* dr_dtype of Q, K, V, O */
+    int32_t reserved0;             /* must be 0 */
+    int64_t stride_b, stride_h, stride_n;   /* in elements; stride of d is 1 */
+} dr_shape;
+
+/* Mask parameters beyond the per-call ones.  NULL means the defaults below. */
+typedef struct {
+    double gamma;        /* decay factor of Eq. 2, > 0.  Default 1.0 */
+    double theta_c;      /* column density threshold, in [0, 1).  Default 0.15 */
+    double theta_m;      /* block activation threshold, in [0, 1).  Default 0.60 */
+    double ratio_far;    /* static mode: ratio for far-field blocks (decay length < Bs); < 0: same as ratio.  Default -1 */
+    int32_t head_fuse;   /* Hf > 0: scores are the mean over heads 0..Hf-1, one mask per batch element;
+                            0: one mask per head.  Default 2 (App. B, head-fusion proxy) */
+    int32_t reserved[7]; /* must be 0 */
+} dr_mask_params;
+
+/* Block classes written by dr_class_map. */
+enum { DR_CLASS_NONE = 0, DR_CLASS_NEAR = 1, DR_CLASS_FAR = 2, DR_CLASS_FORCED = 3 };
+
+/* Create / destroy a context on HIP device `device`.  dr_create allocates nothing on the device yet. */
+dr_status dr_create(dr_ctx** out, int device);
+void dr_destroy(dr_ctx* ctx);
+/* Text of the last error on this context ("" if none).  Valid until the next failing call. */
+const char* dr_last_error(const dr_ctx* ctx);
+
+/*
+ * Candidate geometry of one (shape, lambda, params) as a class byte per block pair.
+ * Paper: window width and split rule (Eqs. 1-6), candidate set (Eq. 7), density
+ * control (theta_c, theta_m), and the never-pruned t <= 1 zone (Eq. 3, Eq. 8).
+ *   class_map  device, [Sb, Sb] bytes, row = query block; DR_CLASS_* values.
+ * A block pair is FORCED if any of its token pairs has temporal distance <= 1.
+ * Otherwise column c of the pair is active if (#rows r with |u_r - v_c| <= w(t)
+ * on a retained frame distance) / (#valid rows) > theta_c, and the pair is a
+ * candidate if (#active columns) / (#valid columns) > theta_m; its class is NEAR
+ * or FAR by the decay length at the smallest temporal distance inside the pair.
+ * Uses Nf, Hg, Wg, Bs, N of `shape` only.  Asynchronous on `stream`.
+ */
+dr_status dr_class_map(dr_ctx* ctx, const dr_shape* shape, double lambda, const dr_mask_params* params,
+                       uint8_t* class_map, void* stream);
+
+/*
+ * Number of candidate block pairs (FORCED + NEAR + FAR) of the geometry: an upper
+ * bound on nnz of any mask dr_build_mask can emit for it, i.e. a safe colidx
+ * capacity per mask.  Synchronous (runs the classification and reads one count back).
+ *   max_selectable_per_row  optional (may be NULL): largest NEAR+FAR count of a row.
+ */
+dr_status dr_mask_capacity(dr_ctx* ctx, const dr_shape* shape, double lambda, const dr_mask_params* params,
+                           int64_t* candidate_blocks, int32_t* max_selectable_per_row);
+
+/*
+ * Stage (a).  Paper: proxy score, Eq. 9, with the fused-head mean of App. B, taken
+ * at block granularity: score[b, m, qb, kb] = mean over heads of mask m of
+ * mean_{p in qb}(Q_p) . mean_{q in kb}(K_q) / sqrt(d), means over valid tokens.
+ *   Q, K      device, dtype/strides of `shape`
+ *   head_fuse Hf in 1..H: masks = 1 (heads 0..Hf-1 averaged); 0: masks = H
+ *   scores    device, float32, contiguous [B, masks, Sb, Sb]
+ */
+dr_status dr_block_scores(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K,
+                          int32_t head_fuse, float* scores, void* stream);
+
+/*
+ * Stage (b).  Paper: Algorithm 1 restated per query-block row at block level.
+ * For each (b, m, qb): kept = FORCED blocks of the row + a selection among the
+ * row's NEAR/FAR blocks (n of them), ordered by score descending, ties by lower
+ * key-block index, -0 equal to +0:
+ *   static  : the first max(1, floor(n * ratio)) of them (Eq. 8's k rule); with
+ *             params->ratio_far >= 0, NEAR and FAR are ranked separately with
+ *             `ratio_or_tau` and `ratio_far`.
+ *   dynamic : e_j = exp(s_j - max s) in fp64, summed one by one in that order;
+ *             the shortest prefix whose sum >= tau * (total sum); at least one
+ *             (the keep-one fallback of Eq. 11 / Algorithm 1).
+ * Output is CSR per mask: rowptr[b, m, 0..Sb] (rowptr[..,0] = 0) and strictly
+ * ascending key-block indices in colidx[b, m, rowptr[qb] .. rowptr[qb+1]).
+ *   mode           dr_mode
+ *   ratio_or_tau   ratio in (0, 1] or tau in (0, 1]
+ *   lambda         long-range factor of Eq. 4, > 0
+ *   scores         device float32 [B, masks, Sb, Sb] (masks from params->head_fuse); must be finite
+ *   rowptr         device int32 [B, masks, Sb + 1]
+ *   colidx         device int32 [B, masks, colidx_capacity]
+ *   colidx_capacity  entries available per mask; > 0
+ *   nnz            device int64 [B, masks]: the number of kept blocks, written even when it
+ *                  exceeds the capacity.  Entries beyond the capacity are never written; the
+ *                  caller must treat a mask with nnz > capacity as invalid.
+ * The first call for a new (geometry, lambda, params) builds and caches the class map
+ * and synchronises once; later calls are fully asynchronous.
+ */
+dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double ratio_or_tau, double lambda,
+                        const dr_mask_params* params, const float* scores,
+                        int32_t* rowptr, int32_t* colidx, int64_t colidx_capacity, int64_t* nnz, void* stream);
+
+/*
+ * Stage (c).  Paper: Eqs. 12-13 with epsilon -> 0: for every valid query token p of
+ * query block qb, O_p = sum_q softmax_q(Q_p . K_q / sqrt(d)) V_q over the valid key
+ * tokens q of the key blocks listed in row qb of the CSR; other keys have weight 0.
+ * A row with no key block yields O = 0 and lse = -inf.  Non-causal.
+ *   Q, K, V, O   device, dtype/strides of `shape` (O is written for valid tokens only)
+ *   rowptr, colidx  device CSR as emitted by dr_build_mask; any well-formed CSR with
+ *                ascending in-range indices is accepted (e.g. the full mask)
+ *   mask_heads   1 (one mask per batch element shared by all heads) or H
+ *   colidx_stride  distance in entries between the colidx arrays of consecutive masks
+ *   lse          optional device float32 [B, H, N]: natural-log sum-exp of each row's logits
+ * bf16 inputs use bf16 MFMA with fp32 accumulation and fp32 softmax; fp32 inputs are
+ * computed in fp32 throughout.
+ */
+dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, const void* V,
+                             const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads,
+                             int64_t colidx_stride, void* O, float* lse, void* stream);
+
+/* Library version string, e.g. "dynamicrad-gfx950 0.1". */
+const char* dr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNAMICRAD_H_ */

@@ -1,0 +1,12 @@
+"""MI355X-native DynamicRad attention hot path: thin Python binding over the C-ABI library.
+
+The three stages (block scores -> mask -> block-sparse attention) run entirely in
+the hand-written gfx950 kernels of ``libdynamicrad.so``; this package only marshals
+torch device pointers and streams into the C calls declared in include/dynamicrad.h.
+There is no CPU fallback: if the library is not built, importing the binding raises.
+"""
+from .binding import (  # noqa: F401
+    Context, DRError, MaskParams, Shape, dr_block_scores, dr_build_mask, dr_class_map, dr_mask_capacity,
+    dr_sparse_attn_fwd, lib_path, load_library, shape_of, version,
+    MODE_STATIC, MODE_DYNAMIC, CLASS_NONE, CLASS_NEAR, CLASS_FAR, CLASS_FORCED,
+)

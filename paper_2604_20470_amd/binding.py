@@ -1,0 +1,161 @@
+"""ctypes binding with the same names as the C entry points (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libdynamicrad.so"
+
+MODE_STATIC, MODE_DYNAMIC = 0, 1
+CLASS_NONE, CLASS_NEAR, CLASS_FAR, CLASS_FORCED = 0, 1, 2, 3
+_STATUS = {0: "DR_OK", 1: "DR_ERR_INVALID_ARG", 2: "DR_ERR_UNSUPPORTED", 3: "DR_ERR_CAPACITY", 4: "DR_ERR_HIP",
+           5: "DR_ERR_NOMEM"}
+
+
+class DRError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {text}")
+        self.status = status
+        self.status_name = _STATUS.get(status, str(status))
+
+
+class Shape(C.Structure):
+    _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("N", C.c_int32), ("d", C.c_int32),
+                ("Nf", C.c_int32), ("Hg", C.c_int32), ("Wg", C.c_int32), ("Bs", C.c_int32),
+                ("dtype", C.c_int32), ("reserved0", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_n", C.c_int64)]
+
+    @property
+    def Sb(self) -> int:
+        return -(-self.N // self.Bs)
+
+
+class MaskParams(C.Structure):
+    _fields_ = [("gamma", C.c_double), ("theta_c", C.c_double), ("theta_m", C.c_double),
+                ("ratio_far", C.c_double), ("head_fuse", C.c_int32), ("reserved", C.c_int32 * 7)]
+
+    def __init__(self, gamma=1.0, theta_c=0.15, theta_m=0.60, ratio_far=-1.0, head_fuse=2):
+        super().__init__(gamma, theta_c, theta_m, ratio_far, head_fuse)
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, _LIB_NAME)
+
+
+_lib = None
+
+
+def load_library():
+    """Load the built library; raises with the build command if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or `python paper_2604_20470_amd/build.py`) first; there is no CPU fallback")
+    lib = C.CDLL(path)
+    vp, i32, i64, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_double
+    shp, mpp = C.POINTER(Shape), C.POINTER(MaskParams)
+    lib.dr_version.restype = C.c_char_p
+    lib.dr_create.argtypes = [C.POINTER(vp), C.c_int]
+    lib.dr_destroy.argtypes = [vp]
+    lib.dr_destroy.restype = None
+    lib.dr_last_error.argtypes = [vp]
+    lib.dr_last_error.restype = C.c_char_p
+    lib.dr_class_map.argtypes = [vp, shp, f64, mpp, vp, vp]
+    lib.dr_mask_capacity.argtypes = [vp, shp, f64, mpp, C.POINTER(i64), C.POINTER(i32)]
+    lib.dr_block_scores.argtypes = [vp, shp, vp, vp, i32, vp, vp]
+    lib.dr_build_mask.argtypes = [vp, shp, i32, f64, f64, mpp, vp, vp, vp, i64, vp, vp]
+    lib.dr_sparse_attn_fwd.argtypes = [vp, shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    for name in ("dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
+                 "dr_sparse_attn_fwd"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def version() -> str:
+    return load_library().dr_version().decode()
+
+
+class Context:
+    """Owns a dr_ctx (scratch + cached candidate geometry) on one device."""
+
+    def __init__(self, device: int = 0):
+        self._lib = load_library()
+        self._h = C.c_void_p()
+        st = self._lib.dr_create(C.byref(self._h), int(device))
+        if st != 0:
+            raise DRError(st, f"dr_create(device={device}) failed")
+        self.device = device
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            self._lib.dr_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def check(self, st: int):
+        if st != 0:
+            raise DRError(st, self._lib.dr_last_error(self._h).decode())
+
+
+def shape_of(t, Nf: int, Hg: int, Wg: int, Bs: int) -> Shape:
+    """Shape descriptor of a [B, H, N, d] torch tensor (Q; K, V, O must share its strides)."""
+    import torch
+    assert t.dim() == 4 and t.stride(3) == 1, "expected [B, H, N, d] with contiguous d"
+    dt = {torch.float32: 0, torch.bfloat16: 1}[t.dtype]
+    B, H, N, d = t.shape
+    return Shape(B, H, N, d, Nf, Hg, Wg, Bs, dt, 0, t.stride(0), t.stride(1), t.stride(2))
+
+
+def _ptr(t) -> C.c_void_p:
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def _pp(params: Optional[MaskParams]):
+    return C.byref(params) if params is not None else None
+
+
+def dr_class_map(ctx: Context, shape: Shape, lam: float, params: Optional[MaskParams], class_map, stream=None):
+    ctx.check(ctx._lib.dr_class_map(ctx._h, C.byref(shape), float(lam), _pp(params), _ptr(class_map), _stream(stream)))
+
+
+def dr_mask_capacity(ctx: Context, shape: Shape, lam: float, params: Optional[MaskParams] = None) -> Tuple[int, int]:
+    cand, msel = C.c_int64(0), C.c_int32(0)
+    ctx.check(ctx._lib.dr_mask_capacity(ctx._h, C.byref(shape), float(lam), _pp(params), C.byref(cand), C.byref(msel)))
+    return cand.value, msel.value
+
+
+def dr_block_scores(ctx: Context, shape: Shape, Q, K, head_fuse: int, scores, stream=None):
+    ctx.check(ctx._lib.dr_block_scores(ctx._h, C.byref(shape), _ptr(Q), _ptr(K), int(head_fuse), _ptr(scores),
+                                       _stream(stream)))
+
+
+def dr_build_mask(ctx: Context, shape: Shape, mode: int, ratio_or_tau: float, lam: float,
+                  params: Optional[MaskParams], scores, rowptr, colidx, colidx_capacity: int, nnz, stream=None):
+    ctx.check(ctx._lib.dr_build_mask(ctx._h, C.byref(shape), int(mode), float(ratio_or_tau), float(lam), _pp(params),
+                                     _ptr(scores), _ptr(rowptr), _ptr(colidx), int(colidx_capacity), _ptr(nnz),
+                                     _stream(stream)))
+
+
+def dr_sparse_attn_fwd(ctx: Context, shape: Shape, Q, K, V, rowptr, colidx, mask_heads: int, colidx_stride: int,
+                       O, lse=None, stream=None):
+    ctx.check(ctx._lib.dr_sparse_attn_fwd(ctx._h, C.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(rowptr),
+                                          _ptr(colidx), int(mask_heads), int(colidx_stride), _ptr(O), _ptr(lse),
+                                          _stream(stream)))

@@ -1,0 +1,343 @@
+// Host layer of the DynamicRad library: argument validation, the fp64 per-t table of the
+// radial window and split rule (paper Eqs. 1-6), scratch management and kernel launches.
+#include "../../include/dynamicrad.h"
+#include "dr_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+
+using namespace dr;
+
+struct dr_ctx {
+    int device = 0;
+    std::string err;
+    // stage (a) scratch
+    float* pooled = nullptr;
+    size_t pooled_bytes = 0;
+    // stage (b) scratch
+    uint32_t* keepbits = nullptr;
+    int32_t* counts = nullptr;
+    size_t keep_bytes = 0, count_bytes = 0;
+    // cached candidate geometry
+    uint8_t* class_map = nullptr;
+    int32_t* row_sel = nullptr;
+    unsigned long long* totals = nullptr;     // device [2]
+    size_t class_bytes = 0, rowsel_bytes = 0;
+    bool geom_valid = false;
+    struct Key { int32_t N, Nf, Nt, Bs; double gamma, lambda, theta_c, theta_m; } key{};
+    int64_t cand_total = 0;
+    int32_t max_sel = 0;
+};
+
+namespace {
+
+dr_status fail(dr_ctx* ctx, dr_status st, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return st;
+}
+
+#define DR_HIP(ctx, call)                                                                          \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) return fail(ctx, DR_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        if (prev != dev) ok = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() {
+        int cur = -1;
+        if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+const dr_mask_params kDefaults = {1.0, 0.15, 0.60, -1.0, 2, {0, 0, 0, 0, 0, 0, 0}};
+
+dr_status grow(dr_ctx* ctx, void** p, size_t* have, size_t need) {
+    if (*have >= need) return DR_OK;
+    if (*p) {
+        DR_HIP(ctx, hipFree(*p));
+        *p = nullptr;
+        *have = 0;
+    }
+    hipError_t e = hipMalloc(p, need);
+    if (e != hipSuccess) {
+        *p = nullptr;
+        return fail(ctx, DR_ERR_NOMEM, "hipMalloc(%zu): %s", need, hipGetErrorString(e));
+    }
+    *have = need;
+    return DR_OK;
+}
+
+dr_status check_geometry(dr_ctx* ctx, const dr_shape* s) {
+    if (!s) return fail(ctx, DR_ERR_INVALID_ARG, "shape is NULL");
+    if (s->Nf <= 0 || s->Hg <= 0 || s->Wg <= 0 || s->N <= 0) return fail(ctx, DR_ERR_INVALID_ARG, "non-positive dimension");
+    if ((int64_t)s->Nf * s->Hg * s->Wg != (int64_t)s->N)
+        return fail(ctx, DR_ERR_INVALID_ARG, "N=%d != Nf*Hg*Wg=%lld", s->N, (long long)s->Nf * s->Hg * s->Wg);
+    if (s->Bs != 32 && s->Bs != 64 && s->Bs != 128) return fail(ctx, DR_ERR_UNSUPPORTED, "Bs=%d not in {32,64,128}", s->Bs);
+    if (s->Nf > kMaxFrames) return fail(ctx, DR_ERR_UNSUPPORTED, "Nf=%d exceeds %d", s->Nf, kMaxFrames);
+    if (s->reserved0 != 0) return fail(ctx, DR_ERR_INVALID_ARG, "reserved0 must be 0");
+    return DR_OK;
+}
+
+dr_status check_tensor_shape(dr_ctx* ctx, const dr_shape* s) {
+    dr_status st = check_geometry(ctx, s);
+    if (st != DR_OK) return st;
+    if (s->B <= 0 || s->H <= 0) return fail(ctx, DR_ERR_INVALID_ARG, "non-positive B or H");
+    if (s->B > 32767 || s->H > 65535) return fail(ctx, DR_ERR_UNSUPPORTED, "B or H too large for the launch grid");
+    if (s->d != 64 && s->d != 128) return fail(ctx, DR_ERR_UNSUPPORTED, "d=%d not in {64,128}", s->d);
+    if (s->dtype != DR_F32 && s->dtype != DR_BF16) return fail(ctx, DR_ERR_INVALID_ARG, "unknown dtype %d", s->dtype);
+    const int64_t es = s->dtype == DR_BF16 ? 2 : 4;
+    if (s->stride_n < s->d || s->stride_h <= 0 || s->stride_b <= 0) return fail(ctx, DR_ERR_INVALID_ARG, "bad strides");
+    if ((s->stride_n * es) % 16 || (s->stride_h * es) % 16 || (s->stride_b * es) % 16)
+        return fail(ctx, DR_ERR_INVALID_ARG, "strides must keep rows 16-byte aligned");
+    return DR_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+dr_status check_params(dr_ctx* ctx, const dr_mask_params* p, double lambda) {
+    if (!(lambda > 0.0) || !std::isfinite(lambda)) return fail(ctx, DR_ERR_INVALID_ARG, "lambda must be > 0");
+    if (!(p->gamma > 0.0) || !std::isfinite(p->gamma)) return fail(ctx, DR_ERR_INVALID_ARG, "gamma must be > 0");
+    if (!(p->theta_c >= 0.0 && p->theta_c < 1.0)) return fail(ctx, DR_ERR_INVALID_ARG, "theta_c must be in [0,1)");
+    if (!(p->theta_m >= 0.0 && p->theta_m < 1.0)) return fail(ctx, DR_ERR_INVALID_ARG, "theta_m must be in [0,1)");
+    if (p->ratio_far > 1.0 || p->ratio_far == 0.0 || std::isnan(p->ratio_far))
+        return fail(ctx, DR_ERR_INVALID_ARG, "ratio_far must be < 0 (unused) or in (0,1]");
+    if (p->head_fuse < 0) return fail(ctx, DR_ERR_INVALID_ARG, "head_fuse must be >= 0");
+    for (int i = 0; i < 7; ++i)
+        if (p->reserved[i] != 0) return fail(ctx, DR_ERR_INVALID_ARG, "reserved fields must be 0");
+    return DR_OK;
+}
+
+// Smallest integer count c in 0..n with c / n > theta (IEEE double division); n + 1 if there is none.
+int32_t min_count_exceeding(int n, double theta) {
+    for (int c = 0; c <= n; ++c)
+        if ((double)c / (double)n > theta) return c;
+    return n + 1;
+}
+
+// Paper Eqs. 1-6, one entry per temporal distance t.
+void fill_frame_table(int Nf, int Nt, int Bs, double gamma, double lambda, FrameTab* tab) {
+    std::memset(tab, 0, sizeof *tab);
+    long long L0 = 1;
+    while (L0 < Nt) L0 <<= 1;                                      // 2^ceil(log2 Nt)
+    for (int t = 0; t < Nf; ++t) {
+        if (t <= 1) {                                              // Eq. 3 first case; never pruned
+            tab->w[t] = Nt;
+            tab->flags[t] = (uint8_t)(1 | (DR_CLASS_FORCED << 1));
+            continue;
+        }
+        int group = 0;                                             // floor(log2 t) + 1 == bit length of t
+        for (int x = t; x > 0; x >>= 1) ++group;
+        const double base = (double)L0 / (double)(1ll << group);
+        const double decay = base * gamma;                         // Eq. 2
+        const double lsplit = base * lambda;                       // Eq. 4
+        const long long rounded = (long long)std::floor(decay + 0.5);
+        const long long w = rounded > Bs ? rounded : Bs;           // Eq. 3
+        long long sf = (long long)std::floor((double)Bs / (lsplit + 1e-6));   // Eq. 5
+        if (sf < 1) sf = 1;
+        const bool retained = (t % sf) == 0;                       // Eq. 6
+        const int cls = decay >= (double)Bs ? DR_CLASS_NEAR : DR_CLASS_FAR;   // Eq. 8 cases
+        tab->w[t] = (int32_t)(w > 0x3fffffff ? 0x3fffffff : w);
+        tab->flags[t] = (uint8_t)((retained ? 1 : 0) | (cls << 1));
+    }
+}
+
+dr_status ensure_geometry(dr_ctx* ctx, const dr_shape* s, double lambda, const dr_mask_params* p, hipStream_t stream) {
+    const int Nt = s->Hg * s->Wg;
+    dr_ctx::Key k{s->N, s->Nf, Nt, s->Bs, p->gamma, lambda, p->theta_c, p->theta_m};
+    if (ctx->geom_valid && std::memcmp(&k, &ctx->key, sizeof k) == 0) return DR_OK;
+    ctx->geom_valid = false;
+    const int Sb = (s->N + s->Bs - 1) / s->Bs;
+    dr_status st;
+    if ((st = grow(ctx, (void**)&ctx->class_map, &ctx->class_bytes, (size_t)Sb * Sb)) != DR_OK) return st;
+    if ((st = grow(ctx, (void**)&ctx->row_sel, &ctx->rowsel_bytes, (size_t)Sb * 4)) != DR_OK) return st;
+    if (!ctx->totals) DR_HIP(ctx, hipMalloc((void**)&ctx->totals, 2 * sizeof(unsigned long long)));
+    Geometry g{};
+    g.N = s->N; g.Nt = Nt; g.Nf = s->Nf; g.Bs = s->Bs; g.Sb = Sb;
+    const int tail = s->N - (Sb - 1) * s->Bs;
+    g.row_min_full = min_count_exceeding(s->Bs, p->theta_c);
+    g.row_min_tail = min_count_exceeding(tail, p->theta_c);
+    g.col_min_full = min_count_exceeding(s->Bs, p->theta_m);
+    g.col_min_tail = min_count_exceeding(tail, p->theta_m);
+    FrameTab tab;
+    fill_frame_table(s->Nf, Nt, s->Bs, p->gamma, lambda, &tab);
+    DR_HIP(ctx, hipMemsetAsync(ctx->totals, 0, 2 * sizeof(unsigned long long), stream));
+    DR_HIP(ctx, launch_class_map(g, tab, ctx->class_map, ctx->row_sel, ctx->totals, stream));
+    unsigned long long host_tot[2] = {0, 0};
+    DR_HIP(ctx, hipMemcpyAsync(host_tot, ctx->totals, sizeof host_tot, hipMemcpyDeviceToHost, stream));
+    DR_HIP(ctx, hipStreamSynchronize(stream));
+    ctx->cand_total = (int64_t)host_tot[0];
+    ctx->max_sel = (int32_t)host_tot[1];
+    std::memcpy(&ctx->key, &k, sizeof k);     // memcmp-compared later: copy padding-free fields bytewise
+    ctx->geom_valid = true;
+    return DR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dr_version(void) { return "dynamicrad-gfx950 0.1"; }
+
+dr_status dr_create(dr_ctx** out, int device) {
+    if (!out) return DR_ERR_INVALID_ARG;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return DR_ERR_INVALID_ARG;
+    dr_ctx* c = new (std::nothrow) dr_ctx();
+    if (!c) return DR_ERR_NOMEM;
+    c->device = device;
+    std::memset(&c->key, 0, sizeof c->key);
+    *out = c;
+    return DR_OK;
+}
+
+void dr_destroy(dr_ctx* ctx) {
+    if (!ctx) return;
+    {
+        DeviceGuard g(ctx->device);
+        void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->row_sel, ctx->totals};
+        for (void* p : ptrs)
+            if (p) (void)hipFree(p);
+    }
+    delete ctx;
+}
+
+const char* dr_last_error(const dr_ctx* ctx) { return ctx ? ctx->err.c_str() : "context is NULL"; }
+
+dr_status dr_class_map(dr_ctx* ctx, const dr_shape* shape, double lambda, const dr_mask_params* params,
+                       uint8_t* class_map, void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    const dr_mask_params* p = params ? params : &kDefaults;
+    dr_status st;
+    if ((st = check_geometry(ctx, shape)) != DR_OK) return st;
+    if ((st = check_params(ctx, p, lambda)) != DR_OK) return st;
+    if (!class_map) return fail(ctx, DR_ERR_INVALID_ARG, "class_map is NULL");
+    DeviceGuard g(ctx->device);
+    hipStream_t s = (hipStream_t)stream;
+    if ((st = ensure_geometry(ctx, shape, lambda, p, s)) != DR_OK) return st;
+    const int Sb = (shape->N + shape->Bs - 1) / shape->Bs;
+    DR_HIP(ctx, hipMemcpyAsync(class_map, ctx->class_map, (size_t)Sb * Sb, hipMemcpyDeviceToDevice, s));
+    return DR_OK;
+}
+
+dr_status dr_mask_capacity(dr_ctx* ctx, const dr_shape* shape, double lambda, const dr_mask_params* params,
+                           int64_t* candidate_blocks, int32_t* max_selectable_per_row) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    const dr_mask_params* p = params ? params : &kDefaults;
+    dr_status st;
+    if ((st = check_geometry(ctx, shape)) != DR_OK) return st;
+    if ((st = check_params(ctx, p, lambda)) != DR_OK) return st;
+    if (!candidate_blocks) return fail(ctx, DR_ERR_INVALID_ARG, "candidate_blocks is NULL");
+    DeviceGuard g(ctx->device);
+    if ((st = ensure_geometry(ctx, shape, lambda, p, nullptr)) != DR_OK) return st;
+    *candidate_blocks = ctx->cand_total;
+    if (max_selectable_per_row) *max_selectable_per_row = ctx->max_sel;
+    return DR_OK;
+}
+
+dr_status dr_block_scores(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, int32_t head_fuse,
+                          float* scores, void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    dr_status st;
+    if ((st = check_tensor_shape(ctx, shape)) != DR_OK) return st;
+    if (!Q || !K || !scores) return fail(ctx, DR_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(Q) || misaligned(K)) return fail(ctx, DR_ERR_INVALID_ARG, "Q/K must be 16-byte aligned");
+    if (head_fuse < 0 || head_fuse > shape->H) return fail(ctx, DR_ERR_INVALID_ARG, "head_fuse=%d outside 0..H", head_fuse);
+    DeviceGuard g(ctx->device);
+    const int Sb = (shape->N + shape->Bs - 1) / shape->Bs;
+    const int Hs = head_fuse > 0 ? head_fuse : shape->H;
+    const int masks = head_fuse > 0 ? 1 : shape->H;
+    const int hpm = head_fuse > 0 ? head_fuse : 1;
+    const size_t need = (size_t)2 * shape->B * Hs * Sb * shape->d * sizeof(float);
+    if ((st = grow(ctx, (void**)&ctx->pooled, &ctx->pooled_bytes, need)) != DR_OK) return st;
+    TensorDesc td{shape->stride_b, shape->stride_h, shape->stride_n, shape->B, shape->H, shape->N, shape->d};
+    hipStream_t s = (hipStream_t)stream;
+    DR_HIP(ctx, launch_pool(Q, K, shape->dtype == DR_BF16, td, Hs, shape->Bs, Sb, ctx->pooled, s));
+    DR_HIP(ctx, launch_scores(ctx->pooled, shape->B, Hs, masks, hpm, Sb, shape->d, scores, s));
+    return DR_OK;
+}
+
+dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double ratio_or_tau, double lambda,
+                        const dr_mask_params* params, const float* scores, int32_t* rowptr, int32_t* colidx,
+                        int64_t colidx_capacity, int64_t* nnz, void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    const dr_mask_params* p = params ? params : &kDefaults;
+    dr_status st;
+    if ((st = check_geometry(ctx, shape)) != DR_OK) return st;
+    if ((st = check_params(ctx, p, lambda)) != DR_OK) return st;
+    if (shape->B <= 0 || shape->H <= 0) return fail(ctx, DR_ERR_INVALID_ARG, "non-positive B or H");
+    if (shape->B > 65535 || shape->H > 65535) return fail(ctx, DR_ERR_UNSUPPORTED, "B or H too large for the launch grid");
+    if (mode != DR_MODE_STATIC_RATIO && mode != DR_MODE_DYNAMIC_THRESHOLD)
+        return fail(ctx, DR_ERR_INVALID_ARG, "unknown mode %d", mode);
+    if (!(ratio_or_tau > 0.0 && ratio_or_tau <= 1.0))
+        return fail(ctx, DR_ERR_INVALID_ARG, "%s must be in (0,1]", mode == DR_MODE_STATIC_RATIO ? "ratio" : "tau");
+    if (p->head_fuse > shape->H) return fail(ctx, DR_ERR_INVALID_ARG, "head_fuse=%d > H", p->head_fuse);
+    if (!scores || !rowptr || !colidx || !nnz) return fail(ctx, DR_ERR_INVALID_ARG, "NULL output or scores pointer");
+    if (colidx_capacity <= 0) return fail(ctx, DR_ERR_CAPACITY, "colidx_capacity must be > 0");
+    DeviceGuard g(ctx->device);
+    hipStream_t s = (hipStream_t)stream;
+    if ((st = ensure_geometry(ctx, shape, lambda, p, s)) != DR_OK) return st;
+    const int Sb = (shape->N + shape->Bs - 1) / shape->Bs;
+    const int masks = p->head_fuse > 0 ? 1 : shape->H;
+    if (ctx->max_sel > kMaxSelectablePerRow)
+        return fail(ctx, DR_ERR_UNSUPPORTED, "%d selectable blocks in a row exceed %d", ctx->max_sel, kMaxSelectablePerRow);
+    const size_t rows = (size_t)shape->B * masks * Sb;
+    const size_t words = (Sb + 31) / 32;
+    if ((st = grow(ctx, (void**)&ctx->keepbits, &ctx->keep_bytes, rows * words * 4)) != DR_OK) return st;
+    if ((st = grow(ctx, (void**)&ctx->counts, &ctx->count_bytes, rows * 4)) != DR_OK) return st;
+    SelectArgs a{};
+    a.mode = mode;
+    a.two_ratio = (mode == DR_MODE_STATIC_RATIO && p->ratio_far > 0.0) ? 1 : 0;
+    a.ratio = ratio_or_tau;
+    a.ratio_far = p->ratio_far;
+    a.tau = ratio_or_tau;
+    int cap = 1;
+    while (cap < ctx->max_sel) cap <<= 1;
+    a.sort_cap = cap;
+    DR_HIP(ctx, launch_select(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
+    DR_HIP(ctx, launch_emit(ctx->keepbits, ctx->counts, shape->B, masks, Sb, rowptr, colidx, colidx_capacity, nnz, s));
+    return DR_OK;
+}
+
+dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, const void* V,
+                             const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads, int64_t colidx_stride,
+                             void* O, float* lse, void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    dr_status st;
+    if ((st = check_tensor_shape(ctx, shape)) != DR_OK) return st;
+    if (!Q || !K || !V || !O || !rowptr || !colidx) return fail(ctx, DR_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(ctx, DR_ERR_INVALID_ARG, "Q/K/V/O must be 16-byte aligned");
+    if (mask_heads != 1 && mask_heads != shape->H) return fail(ctx, DR_ERR_INVALID_ARG, "mask_heads must be 1 or H");
+    if (colidx_stride < 0) return fail(ctx, DR_ERR_INVALID_ARG, "negative colidx_stride");
+    DeviceGuard g(ctx->device);
+    AttnArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
+    a.rowptr = rowptr; a.colidx = colidx; a.colidx_stride = colidx_stride; a.mask_heads = mask_heads;
+    a.td = TensorDesc{shape->stride_b, shape->stride_h, shape->stride_n, shape->B, shape->H, shape->N, shape->d};
+    a.Bs = shape->Bs;
+    a.Sb = (shape->N + shape->Bs - 1) / shape->Bs;
+    a.bf16 = shape->dtype == DR_BF16;
+    hipStream_t s = (hipStream_t)stream;
+    if (attn_mfma_supported(a)) DR_HIP(ctx, launch_attn_mfma(a, s));
+    else DR_HIP(ctx, launch_attn_generic(a, s));
+    return DR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+// Internal declarations shared by the host layer and the gfx950 kernels.
+// Nothing here is part of the public ABI (see include/dynamicrad.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dr {
+
+constexpr int kMaxFrames = 256;          // per-t table travels as a kernel argument
+constexpr int kMaxSelectablePerRow = 8192;
+
+// Per temporal distance t (paper Eqs. 1-6, evaluated on the host in fp64).
+struct FrameTab {
+    int32_t w[kMaxFrames];       // window half-width of Eq. 3
+    uint8_t flags[kMaxFrames];   // bit0: frame distance retained (Eq. 6); bits 1-2: DR_CLASS_* of Eq. 8's cases
+};
+
+struct Geometry {
+    int32_t N, Nt, Nf, Bs, Sb;
+    // smallest integer count c with c / n > theta, for full blocks and for the partial last block
+    int32_t row_min_full, row_min_tail;   // theta_c against the number of valid rows
+    int32_t col_min_full, col_min_tail;   // theta_m against the number of valid columns
+};
+
+struct TensorDesc {
+    int64_t stride_b, stride_h, stride_n;   // elements
+    int32_t B, H, N, d;
+};
+
+// ---- stage (a) -------------------------------------------------------------------------
+// pooled[which][b][hs][blk][d] = mean over the valid tokens of block blk; which 0 = Q, 1 = K.
+hipError_t launch_pool(const void* Q, const void* K, bool bf16, const TensorDesc& td, int Hs, int Bs, int Sb,
+                       float* pooled, hipStream_t s);
+// scores[b][m][qb][kb] = (1 / (heads_per_mask * sqrt(d))) * sum_h qbar . kbar
+hipError_t launch_scores(const float* pooled, int B, int Hs, int masks, int heads_per_mask, int Sb, int d,
+                         float* scores, hipStream_t s);
+
+// ---- stage (b) -------------------------------------------------------------------------
+// class_map[qb][kb]; row_sel[qb] = NEAR+FAR count of the row; totals[0] += candidates, totals[1] = max row_sel.
+hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* class_map, int32_t* row_sel,
+                            unsigned long long* totals, hipStream_t s);
+struct SelectArgs {
+    int32_t mode;            // 0 static, 1 dynamic
+    int32_t two_ratio;       // static: rank NEAR and FAR separately
+    double ratio, ratio_far, tau;
+    int32_t sort_cap;        // power of two >= the largest selectable count of a row
+};
+// keepbits[(b*masks+m)*Sb + qb][words], counts[(b*masks+m)*Sb + qb]
+hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
+                         const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
+hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb,
+                       int32_t* rowptr, int32_t* colidx, int64_t capacity, int64_t* nnz, hipStream_t s);
+
+// ---- stage (c) -------------------------------------------------------------------------
+struct AttnArgs {
+    const void *Q, *K, *V;
+    void* O;
+    float* lse;                  // nullable
+    const int32_t* rowptr;       // [B, mask_heads, Sb+1]
+    const int32_t* colidx;       // [B, mask_heads, colidx_stride]
+    int64_t colidx_stride;
+    int32_t mask_heads;
+    TensorDesc td;
+    int32_t Bs, Sb;
+    int32_t bf16;
+};
+// Any d in {64,128}, Bs in {32,64,128}, f32 or bf16 storage; arithmetic in fp32 on the vector ALUs.
+hipError_t launch_attn_generic(const AttnArgs& a, hipStream_t s);
+// bf16 storage, d = 128, Bs = 128: MFMA path.  Returns hipErrorNotSupported for other shapes.
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
+bool attn_mfma_supported(const AttnArgs& a);
+
+}  // namespace dr

@@ -1,0 +1,293 @@
+// Stage (b): candidate geometry, per-row selection and CSR emission.  gfx950 only.
+//
+//   k_class_map  integer interval arithmetic on the radial window (paper Eqs. 3, 6, 7 and the
+//                density rule); one wavefront classifies one (query block, key block) pair,
+//                lanes own columns, ballots count active columns.
+//   k_select     one workgroup per (batch, mask, query block) row: compacts the selectable
+//                blocks into LDS as 64-bit sort keys, bitonic-sorts them, then takes the
+//                static top-k or the dynamic cumulative-mass prefix (paper Eq. 8 k rule;
+//                keep-one fallback of Eq. 11 / Algorithm 1).
+//   k_emit       per row: offset = sum of the previous rows' counts, bit-expansion to
+//                ascending key-block indices.
+#include "dr_internal.h"
+
+namespace dr {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// grid: (Sb)   one workgroup per query block, waves stride over key blocks
+__global__ __launch_bounds__(kThreads) void k_class_map(Geometry g, FrameTab tab, uint8_t* __restrict__ class_map,
+                                                        int32_t* __restrict__ row_sel,
+                                                        unsigned long long* __restrict__ totals) {
+    __shared__ int s_sel, s_cand;
+    const int qb = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    if (threadIdx.x == 0) { s_sel = 0; s_cand = 0; }
+    __syncthreads();
+    const int r0 = qb * g.Bs, r1 = min(g.N, r0 + g.Bs);
+    const int i0 = r0 / g.Nt, i1 = (r1 - 1) / g.Nt;
+    const int row_min = (r1 - r0 == g.Bs) ? g.row_min_full : g.row_min_tail;
+    int n_sel = 0, n_cand = 0;
+    for (int kb = wave; kb < g.Sb; kb += kWaves) {
+        const int c0 = kb * g.Bs, c1 = min(g.N, c0 + g.Bs);
+        const int j0 = c0 / g.Nt, j1 = (c1 - 1) / g.Nt;
+        const int gap = max(0, max(j0 - i1, i0 - j1));
+        int cls;
+        if (gap <= 1) {
+            cls = 3;
+        } else {
+            int n_active = 0;
+            for (int cbase = 0; cbase < c1 - c0; cbase += 64) {
+                const int col = cbase + lane;
+                bool active = false;
+                if (col < c1 - c0) {
+                    const int q = c0 + col;
+                    const int j = q / g.Nt, v = q - j * g.Nt;
+                    int cnt = 0;
+                    for (int i = i0; i <= i1; ++i) {
+                        const int t = abs(i - j);
+                        if (tab.flags[t] & 1) {
+                            const int w = tab.w[t];
+                            const int u_lo = max(r0, i * g.Nt) - i * g.Nt;
+                            const int u_hi = min(r1, (i + 1) * g.Nt) - 1 - i * g.Nt;
+                            cnt += max(0, min(u_hi, v + w) - max(u_lo, v - w) + 1);
+                        }
+                    }
+                    active = cnt >= row_min;
+                }
+                n_active += __popcll(__ballot(active));
+            }
+            const int col_min = (c1 - c0 == g.Bs) ? g.col_min_full : g.col_min_tail;
+            cls = (n_active >= col_min) ? ((tab.flags[gap] >> 1) & 3) : 0;
+        }
+        if (lane == 0) class_map[(int64_t)qb * g.Sb + kb] = (uint8_t)cls;
+        n_cand += (cls != 0);
+        n_sel += (cls == 1 || cls == 2);
+    }
+    if (lane == 0) { atomicAdd(&s_sel, n_sel); atomicAdd(&s_cand, n_cand); }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        row_sel[qb] = s_sel;
+        atomicAdd(&totals[0], (unsigned long long)s_cand);
+        atomicMax(&totals[1], (unsigned long long)s_sel);
+    }
+}
+
+// Sort key, ascending order == (NEAR before FAR when ranked separately), score descending, kb ascending.
+//   bit 63      far flag (only when the two classes are ranked separately)
+//   bits 62..31 bitwise complement of the order-preserving integer image of the score
+//   bits 30..0  key-block index
+__device__ __forceinline__ uint64_t make_key(float s, int kb, bool far_bit) {
+    s = s + 0.0f;                                  // -0 -> +0
+    uint32_t u = __float_as_uint(s);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending unsigned == ascending float
+    u = ~u;                                        // descending
+    return ((uint64_t)(far_bit ? 1 : 0) << 63) | ((uint64_t)u << 31) | (uint64_t)(uint32_t)kb;
+}
+__device__ __forceinline__ float key_score(uint64_t key) {
+    uint32_t u = ~(uint32_t)(key >> 31);
+    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+    return __uint_as_float(u);
+}
+__device__ __forceinline__ int key_block(uint64_t key) { return (int)(key & 0x7fffffffu); }
+
+__device__ __forceinline__ int keep_count(int n, double ratio) {
+    if (n == 0) return 0;
+    const int k = (int)floor((double)n * ratio);
+    return max(1, k);
+}
+
+// grid: (Sb, masks, B).  LDS: keys[sort_cap] u64 | mass[sort_cap] f64 (dynamic mode) | keep[words] u32
+__global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__ class_map,
+                                                     const float* __restrict__ scores, int masks, int Sb,
+                                                     SelectArgs a, uint32_t* __restrict__ keepbits,
+                                                     int32_t* __restrict__ counts) {
+    extern __shared__ unsigned char smem[];
+    uint64_t* keys = reinterpret_cast<uint64_t*>(smem);
+    double* mass = reinterpret_cast<double*>(smem + (size_t)a.sort_cap * 8);
+    const int words = (Sb + 31) / 32;
+    uint32_t* keep = reinterpret_cast<uint32_t*>(smem + (size_t)a.sort_cap * (a.mode == 1 ? 16 : 8));
+    __shared__ int s_n, s_near, s_k, s_cnt;
+
+    const int qb = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int64_t row = ((int64_t)b * masks + m) * Sb + qb;
+    const float* srow = scores + row * Sb;
+    const uint8_t* crow = class_map + (int64_t)qb * Sb;
+
+    for (int i = tid; i < words; i += kThreads) keep[i] = 0u;
+    if (tid == 0) { s_n = 0; s_near = 0; s_k = 0x7fffffff; s_cnt = 0; }
+    __syncthreads();
+    for (int kb = tid; kb < Sb; kb += kThreads) {
+        const int c = crow[kb];
+        if (c == 3) {
+            atomicOr(&keep[kb >> 5], 1u << (kb & 31));
+        } else if (c != 0) {
+            const int pos = atomicAdd(&s_n, 1);
+            const bool far_bit = a.two_ratio && c == 2;
+            if (a.two_ratio && c == 1) atomicAdd(&s_near, 1);
+            keys[pos] = make_key(srow[kb], kb, far_bit);
+        }
+    }
+    __syncthreads();
+    const int n = s_n;
+    if (n > 0) {
+        int P = 1;
+        while (P < n) P <<= 1;
+        for (int i = n + tid; i < P; i += kThreads) keys[i] = ~0ull;
+        __syncthreads();
+        for (int k = 2; k <= P; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int i = tid; i < P; i += kThreads) {
+                    const int ixj = i ^ j;
+                    if (ixj > i) {
+                        const uint64_t x = keys[i], y = keys[ixj];
+                        const bool up = (i & k) == 0;
+                        if ((x > y) == up) { keys[i] = y; keys[ixj] = x; }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        if (a.mode == 0) {
+            if (a.two_ratio) {
+                const int n_near = s_near;
+                const int k_near = keep_count(n_near, a.ratio), k_far = keep_count(n - n_near, a.ratio_far);
+                for (int i = tid; i < n; i += kThreads) {
+                    const bool sel = (i < n_near) ? (i < k_near) : (i - n_near < k_far);
+                    if (sel) { const int kb = key_block(keys[i]); atomicOr(&keep[kb >> 5], 1u << (kb & 31)); }
+                }
+            } else {
+                const int k = keep_count(n, a.ratio);
+                for (int i = tid; i < k; i += kThreads) {
+                    const int kb = key_block(keys[i]);
+                    atomicOr(&keep[kb >> 5], 1u << (kb & 31));
+                }
+            }
+        } else {
+            const double top = (double)key_score(keys[0]);
+            for (int i = tid; i < n; i += kThreads) mass[i] = exp((double)key_score(keys[i]) - top);
+            __syncthreads();
+            if (tid == 0) {          // one-by-one summation in the total order: the order is part of the definition
+                double cum = 0.0;
+                for (int i = 0; i < n; ++i) { cum = cum + mass[i]; mass[i] = cum; }
+            }
+            __syncthreads();
+            const double target = a.tau * mass[n - 1];
+            for (int i = tid; i < n; i += kThreads)
+                if (mass[i] >= target && (i == 0 || !(mass[i - 1] >= target))) atomicMin(&s_k, i + 1);
+            __syncthreads();
+            const int k = max(1, min(n, s_k));
+            for (int i = tid; i < k; i += kThreads) {
+                const int kb = key_block(keys[i]);
+                atomicOr(&keep[kb >> 5], 1u << (kb & 31));
+            }
+        }
+    }
+    __syncthreads();
+    int c = 0;
+    for (int i = tid; i < words; i += kThreads) {
+        const uint32_t wv = keep[i];
+        keepbits[row * words + i] = wv;
+        c += __popc(wv);
+    }
+    for (int off = 32; off > 0; off >>= 1) c += __shfl_down(c, off);
+    if (lane_id() == 0) atomicAdd(&s_cnt, c);
+    __syncthreads();
+    if (tid == 0) counts[row] = s_cnt;
+}
+
+// grid: (Sb, masks, B)
+__global__ __launch_bounds__(kThreads) void k_emit(const uint32_t* __restrict__ keepbits,
+                                                   const int32_t* __restrict__ counts, int masks, int Sb,
+                                                   int32_t* __restrict__ rowptr, int32_t* __restrict__ colidx,
+                                                   int64_t capacity, int64_t* __restrict__ nnz) {
+    __shared__ long long s_off;
+    __shared__ int s_wave[kWaves];
+    const int qb = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int64_t mask_id = (int64_t)b * masks + m;
+    const int64_t row = mask_id * Sb + qb;
+    const int words = (Sb + 31) / 32;
+    if (tid == 0) s_off = 0;
+    __syncthreads();
+    long long part = 0;
+    for (int i = tid; i < qb; i += kThreads) part += counts[mask_id * Sb + i];
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off);
+    if (lane == 0 && part) atomicAdd((unsigned long long*)&s_off, (unsigned long long)part);
+    __syncthreads();
+    const long long off0 = s_off;
+    if (tid == 0) {
+        rowptr[mask_id * (Sb + 1) + qb] = (int32_t)off0;
+        if (qb == Sb - 1) {
+            const long long total = off0 + counts[row];
+            rowptr[mask_id * (Sb + 1) + Sb] = (int32_t)total;
+            nnz[mask_id] = total;
+        }
+    }
+    int32_t* out = colidx + mask_id * capacity;
+    long long base = off0;
+    for (int w0 = 0; w0 < words; w0 += kThreads) {
+        const int wi = w0 + tid;
+        const uint32_t wv = (wi < words) ? keepbits[row * words + wi] : 0u;
+        const int c = __popc(wv);
+        // exclusive prefix of c over the workgroup
+        int incl = c;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int wave_base = 0, total = 0;
+        for (int i = 0; i < kWaves; ++i) {
+            if (i < wave) wave_base += s_wave[i];
+            total += s_wave[i];
+        }
+        long long pos = base + wave_base + incl - c;
+        uint32_t bits = wv;
+        while (bits) {
+            const int bit = __ffs(bits) - 1;
+            bits &= bits - 1;
+            if (pos < capacity) out[pos] = wi * 32 + bit;
+            ++pos;
+        }
+        base += total;
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* class_map, int32_t* row_sel,
+                            unsigned long long* totals, hipStream_t s) {
+    hipLaunchKernelGGL(k_class_map, dim3(g.Sb), dim3(kThreads), 0, s, g, tab, class_map, row_sel, totals);
+    return hipGetLastError();
+}
+
+hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
+                         const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s) {
+    const size_t words = (Sb + 31) / 32;
+    const size_t lds = (size_t)a.sort_cap * (a.mode == 1 ? 16 : 8) + words * 4;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k_select, dim3(Sb, masks, B), dim3(kThreads), lds, s, class_map, scores, masks, Sb, a,
+                       keepbits, counts);
+    return hipGetLastError();
+}
+
+hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb,
+                       int32_t* rowptr, int32_t* colidx, int64_t capacity, int64_t* nnz, hipStream_t s) {
+    hipLaunchKernelGGL(k_emit, dim3(Sb, masks, B), dim3(kThreads), 0, s, keepbits, counts, masks, Sb, rowptr, colidx,
+                       capacity, nnz);
+    return hipGetLastError();
+}
+
+}  // namespace dr

@@ -1,0 +1,54 @@
+"""CPU-only checks of the boundary: the library loads and exports what the header declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2604_20470_amd as dr
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "dynamicrad.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dr_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_stage_calls():
+    names = _declared()
+    for n in ("dr_block_scores", "dr_build_mask", "dr_sparse_attn_fwd", "dr_create", "dr_destroy", "dr_last_error"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = dr.load_library()
+    for n in _declared():
+        assert hasattr(lib, n), n
+    assert dr.version().startswith("dynamicrad-gfx950")
+
+
+def test_struct_layouts_match_header():
+    # dr_shape: 10 int32 + 3 int64 = 64 bytes; dr_mask_params: 4 doubles + 8 int32 = 64 bytes
+    assert ctypes.sizeof(dr.Shape) == 64
+    assert ctypes.sizeof(dr.MaskParams) == 64
+    p = dr.MaskParams()
+    assert (p.gamma, p.theta_c, p.theta_m, p.ratio_far, p.head_fuse) == (1.0, 0.15, 0.60, -1.0, 2)
+
+
+def test_no_gpu_means_loud_failure_not_fallback():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(dr.DRError):
+        dr.Context(0)
+
+
+def test_product_does_not_import_oracle():
+    pkg = os.path.join(ROOT, "paper_2604_20470_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.replace("no CPU fallback", ""), f

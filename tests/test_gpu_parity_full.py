@@ -1,0 +1,86 @@
+"""GPU parity at the benchmark configurations (full sizes, the launch configuration bench.py times).
+
+Scores and masks are compared in full.  The oracle's attention at these sizes would take
+minutes per head, so attention is compared on a seeded sample of (head, query block) rows --
+rows are independent, each sampled row is checked element by element: the first and last
+block (ragged tail), blocks straddling a frame boundary, and random ones.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_20470_amd as dr
+from oracle import dynamicrad_oracle as o
+from workloads import CONFIGS
+
+from helpers import GpuRun, assert_masks_equal, oracle_class_map, oracle_masks_from, score_error, to_f64
+from test_gpu_parity import ATTN_TOL, SCORE_TOL, _attention_check
+
+pytestmark = pytest.mark.gpu
+
+
+def _mode_par(wl, cls):
+    if wl.mode == "dynamic":
+        return "dynamic", wl.tau
+    if wl.ratio is not None:
+        return "static", wl.ratio
+    return "static", o.ratio_for_target_sparsity(cls, wl.target_sparsity)
+
+
+def _sample_rows(wl, rng, n_random):
+    Sb, Bs, Nt = wl.Sb, wl.Bs, wl.Nt
+    straddle = [qb for qb in range(Sb) if (qb * Bs) // Nt != (min(wl.N, qb * Bs + Bs) - 1) // Nt]
+    rows = {0, Sb - 1}
+    rows.update(rng.choice(straddle, size=min(2, len(straddle)), replace=False).tolist() if straddle else [])
+    rows.update(rng.integers(0, Sb, n_random).tolist())
+    return sorted(rows)
+
+
+@pytest.mark.parametrize("name,heads,n_heads_attn,n_rows", [
+    ("cfg2", None, 3, 6),
+    ("cfg3", [0, 1, 7, 39], 2, 4),
+    ("cfg4", [0, 1, 22], 2, 3),
+    ("cfg5", [0, 1, 13], 2, 3),
+])
+def test_config_pipeline(name, heads, n_heads_attn, n_rows):
+    wl = CONFIGS[name]
+    rng = np.random.default_rng(1000 + wl.index)
+    run = GpuRun(wl, heads=heads)
+    print(f"[{name}] N={wl.N} Sb={wl.Sb} heads={run.heads}", flush=True)
+    cls = oracle_class_map(wl)
+    assert (run.class_map().cpu().numpy() == cls).all()
+    # (a) fused-head scores (heads 0, 1 of the workload are generated first in every subset)
+    scores = run.block_scores()
+    want = o.block_scores(to_f64(run.Qc[:, :2]), to_f64(run.Kc[:, :2]), wl.Bs, 2)
+    err = score_error(scores, want)
+    print(f"[{name}] score err {err:.2e}", flush=True)
+    assert err <= SCORE_TOL
+    # (b) mask from the GPU's fp32 scores, bit-exact
+    mode, par = _mode_par(wl, cls)
+    rowptr, colidx, nnz, cap = run.build_mask(scores, mode, par)
+    masks = oracle_masks_from(scores, cls, mode, par)
+    assert_masks_equal(rowptr, colidx, nnz, masks)
+    sparsity = o.effective_sparsity(masks[0][0][0], wl.Sb)
+    print(f"[{name}] {mode} par={par} nnz={int(nnz[0, 0])} sparsity={sparsity:.4f}", flush=True)
+    if wl.target_sparsity:
+        assert sparsity >= wl.target_sparsity
+    # (c) attention on sampled rows
+    hs = rng.choice(len(run.heads), size=n_heads_attn, replace=False).tolist()
+    sample = [(0, hi, _sample_rows(wl, rng, n_rows)) for hi in hs]
+    worst = _attention_check(run, rowptr, colidx, cap, sample, ATTN_TOL[wl.dtype])
+    print(f"[{name}] attention max-abs err {worst:.3e} on {sample}", flush=True)
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
+def test_per_head_masks_full(name):
+    """head_fuse = 0: one mask per head, both modes, selection bit-exact on every head generated."""
+    wl = CONFIGS[name]
+    heads = None if name == "cfg2" else [0, 5, 17]
+    run = GpuRun(wl, heads=heads, params=dr.MaskParams(head_fuse=0))
+    scores = run.block_scores()
+    want = o.block_scores(to_f64(run.Qc), to_f64(run.Kc), wl.Bs, 0)
+    assert score_error(scores, want) <= SCORE_TOL
+    cls = oracle_class_map(wl)
+    for mode, par in (("static", 0.2), ("dynamic", 0.9)):
+        rowptr, colidx, nnz, cap = run.build_mask(scores, mode, par)
+        assert_masks_equal(rowptr, colidx, nnz, oracle_masks_from(scores, cls, mode, par))
