@@ -95,8 +95,8 @@ def test_masks_bit_exact_small(wl, head_fuse):
 
 def test_masks_two_ratio_and_ties():
     wl = tiny_case("tiny8", Nf=12, lam=2.0)
-    run = GpuRun(wl, params=dr.MaskParams(head_fuse=0, ratio_far=0.25, gamma=1.0))
-    cls = oracle_class_map(wl, lam=2.0)
+    run = GpuRun(wl, params=dr.MaskParams(head_fuse=0, ratio_far=0.25, gamma=3.0))
+    cls = oracle_class_map(wl, gamma=3.0, lam=2.0)
     assert (cls == 1).any() and (cls == 2).any()
     scores = run.block_scores()
     rowptr, colidx, nnz, cap = run.build_mask(scores, "static", 0.6)
