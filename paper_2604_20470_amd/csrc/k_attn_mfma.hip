@@ -40,8 +40,17 @@ constexpr int kStageBytes = 2 * kTileBytes;          // K then V
 constexpr int kLdsBytes = 2 * kStageBytes;           // two stages: 64 KB
 constexpr int kPieces = kTileBytes / 1024;           // 1 KB wave-wide load instructions per operand tile
 
-#define DR_LDS(p) ((__attribute__((address_space(3))) void*)(p))
-#define DR_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
+// Issued through inline assembly so that the compiler's wait-count insertion does not see an LDS write it
+// cannot disambiguate (it would drain the prefetch before every LDS read); completion is tracked by hand
+// with the vmcnt waits in the main loop.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gptr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
 // The barrier carries no memory fence on purpose: a fence would drain the prefetch of the next
 // chunk.  Ordering of the direct-to-LDS loads is enforced by the explicit vmcnt waits below.
 #define DR_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
@@ -62,16 +71,23 @@ template <int NQ>
 __device__ __forceinline__ void issue_chunk(const char* Kh, const char* Vh, int64_t row_bytes, int key0, int last_row,
                                             unsigned char* stage, int wave, int lane) {
     const int r_in = lane >> 4, piece = lane & 15;
+    const uint32_t stage_addr = lds_addr(stage);
 #pragma unroll
     for (int i = 0; i < kPieces / Cfg<NQ>::kWaves; ++i) {
         const int p = wave + i * Cfg<NQ>::kWaves;      // 1 KB piece index = rows 4p .. 4p+3
         const int r = p * 4 + r_in;
         const int row = min(key0 + r, last_row);      // rows past the end re-read the last valid row (masked later)
         const int64_t off = (int64_t)row * row_bytes;
-        __builtin_amdgcn_global_load_lds(DR_GLB(Kh + off + ((piece ^ (r & 15)) << 4)), DR_LDS(stage + p * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(DR_GLB(Vh + off + ((piece ^ ((r & 3) << 2)) << 4)),
-                                         DR_LDS(stage + kTileBytes + p * 1024), 16, 0, 0);
+        dma16(Kh + off + ((piece ^ (r & 15)) << 4), __builtin_amdgcn_readfirstlane(stage_addr + p * 1024));
+        dma16(Vh + off + ((piece ^ ((r & 3) << 2)) << 4),
+              __builtin_amdgcn_readfirstlane(stage_addr + kTileBytes + p * 1024));
     }
+}
+
+// max of a value with its copy in the lane 32 away (v_permlane32_swap: no LDS round trip)
+__device__ __forceinline__ float max_across_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 __device__ __forceinline__ v8bf pack8(const v16f& c, int base, float cs, float mneg, float& sum) {
@@ -85,13 +101,21 @@ __device__ __forceinline__ v8bf pack8(const v16f& c, int base, float cs, float m
     return out;
 }
 
-// grid: (Sb, H, B)
+// grid: (Sb * H * B) in one dimension.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own
+// L2; id -> work item is remapped so that one XCD walks a contiguous run of (batch, head, query block) items:
+// the workgroups resident on an XCD at any time are then neighbouring query blocks of one head, whose kept key
+// blocks largely coincide (the forced zone of a frame), and their K/V tiles are served from that XCD's L2.
 template <int NQ>
 __global__ __launch_bounds__(Cfg<NQ>::kThreads) __attribute__((amdgpu_waves_per_eu(NQ == 1 ? 2 : 1, NQ == 1 ? 2 : 1))) void k_attn_mfma(AttnArgs a) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int qb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    constexpr int kXcds = 8;
+    const int total_items = a.Sb * a.td.H * a.td.B;
+    const int per_xcd = (total_items + kXcds - 1) / kXcds;
+    const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (item >= total_items) return;
+    const int qb = item % a.Sb, h = (item / a.Sb) % a.td.H, b = item / (a.Sb * a.td.H);
     const int N = a.td.N;
     const int64_t row_bytes = a.td.stride_n * 2;
     const int64_t head_off = ((int64_t)b * a.td.stride_b + (int64_t)h * a.td.stride_h) * 2;
@@ -137,6 +161,7 @@ __global__ __launch_bounds__(Cfg<NQ>::kThreads) __attribute__((amdgpu_waves_per_
     auto chunk_key0 = [&](int c) { return __builtin_amdgcn_readfirstlane(ci[beg + (c >> 1)]) * kBs + (c & 1) * kChunkKeys; };
 
     if (total_chunks > 0) issue_chunk<NQ>(Kh, Vh, row_bytes, chunk_key0(0), N - 1, smem, wave, lane);
+    wait_vmcnt<0>();
 
     // per-lane LDS read offsets
     const int v_e = (lane & 15) >> 2, v_c = lane & 3, v_grp = (lane >> 4) & 1;
@@ -144,13 +169,11 @@ __global__ __launch_bounds__(Cfg<NQ>::kThreads) __attribute__((amdgpu_waves_per_
     for (int c = 0; c < total_chunks; ++c) {
         unsigned char* stage = smem + (c & 1) * kStageBytes;
         const int key0 = chunk_key0(c);
-        if (c + 1 < total_chunks) {
-            issue_chunk<NQ>(Kh, Vh, row_bytes, chunk_key0(c + 1), N - 1, smem + ((c + 1) & 1) * kStageBytes, wave, lane);
-            wait_vmcnt<Cfg<NQ>::kLoadsPerChunk>();
-        } else {
-            wait_vmcnt<0>();
-        }
+        // One barrier per chunk: past it, every wave's share of chunk c has landed (each wave waited for its own
+        // loads before arriving) and every wave has finished reading chunk c-1, whose stage the next loads reuse.
         DR_BARRIER();
+        if (c + 1 < total_chunks)
+            issue_chunk<NQ>(Kh, Vh, row_bytes, chunk_key0(c + 1), N - 1, smem + ((c + 1) & 1) * kStageBytes, wave, lane);
 
         // ---- S^T = K Q^T : [64 keys x 32*NQ queries] ----
         v16f s[NQ][2];
@@ -160,17 +183,45 @@ __global__ __launch_bounds__(Cfg<NQ>::kThreads) __attribute__((amdgpu_waves_per_
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) s[nq][mb][j] = 0.f;
+        {
+            v8bf kf[2][8];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
+            for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const int r = mb * 32 + l32;
-                const v8bf kf = *reinterpret_cast<const v8bf*>(stage + r * kRowBytes + (((ks * 2 + half) ^ (r & 15)) << 4));
+                for (int mb = 0; mb < 2; ++mb) {
+                    const int r = mb * 32 + l32;
+                    kf[mb][ks] = *reinterpret_cast<const v8bf*>(stage + r * kRowBytes + (((ks * 2 + half) ^ (r & 15)) << 4));
+                }
 #pragma unroll
-                for (int nq = 0; nq < NQ; ++nq)
-                    s[nq][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nq][ks], s[nq][mb], 0, 0, 0);
-            }
+            for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq)
+                        s[nq][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][ks], qf[nq][ks], s[nq][mb], 0, 0, 0);
         }
+        // V^T fragments for the second product: issued now so that they land while the softmax runs
+        const unsigned char* vt = stage + kTileBytes;
+        v8bf vf[2][2][4];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                const int r_lo = mb * 32 + st * 16 + half * 4 + v_e;     // keys r_lo (i<4) and r_lo + 8 (i>=4)
+                const int r_hi = r_lo + 8;
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    const int piece = db * 4 + v_grp * 2 + (v_c >> 1);
+                    const int sub = (v_c & 1) * 8;
+                    union { struct { v4s a, b; } s2; v8bf v; } u;
+                    u.s2.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) v4s*)(vt + r_lo * kRowBytes + ((piece ^ ((r_lo & 3) << 2)) << 4) + sub));
+                    u.s2.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) v4s*)(vt + r_hi * kRowBytes + ((piece ^ ((r_hi & 3) << 2)) << 4) + sub));
+                    vf[mb][st][db] = u.v;
+                }
+            }
+        __builtin_amdgcn_sched_barrier(0);
         // keys past the end of the sequence (only in the last block)
         const int valid = N - key0;
         if (valid < kChunkKeys) {
@@ -192,7 +243,7 @@ __global__ __launch_bounds__(Cfg<NQ>::kThreads) __attribute__((amdgpu_waves_per_
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[nq][mb][j]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            mx = max_across_halves(mx);
             const float m_new = fmaxf(m_run[nq], mx);               // finite: every chunk holds a valid key
             const float alpha = __builtin_amdgcn_exp2f((m_run[nq] - m_new) * cs);
             m_run[nq] = m_new;
@@ -212,31 +263,18 @@ __global__ __launch_bounds__(Cfg<NQ>::kThreads) __attribute__((amdgpu_waves_per_
         }
 
         // ---- O^T += V^T P^T ----
-        const unsigned char* vt = stage + kTileBytes;
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
+        for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int st = 0; st < 2; ++st) {
-                const int r_lo = mb * 32 + st * 16 + half * 4 + v_e;     // keys r_lo (i<4) and r_lo + 8 (i>=4)
-                const int r_hi = r_lo + 8;
+            for (int st = 0; st < 2; ++st)
 #pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const int piece = db * 4 + v_grp * 2 + (v_c >> 1);
-                    const int sub = (v_c & 1) * 8;
-                    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) v4s*)(vt + r_lo * kRowBytes + ((piece ^ ((r_lo & 3) << 2)) << 4) + sub));
-                    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) v4s*)(vt + r_hi * kRowBytes + ((piece ^ ((r_hi & 3) << 2)) << 4) + sub));
-                    union { struct { v4s a, b; } s2; v8bf v; } u;
-                    u.s2.a = lo;
-                    u.s2.b = hi;
+                for (int db = 0; db < 4; ++db)
 #pragma unroll
                     for (int nq = 0; nq < NQ; ++nq)
-                        o[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[nq][mb][st], o[nq][db], 0, 0, 0);
-                }
-            }
-        }
-        DR_BARRIER();   // everyone is done with this stage before the loads of chunk c+2 overwrite it
+                        o[nq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mb][st][db], pf[nq][mb][st], o[nq][db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);   // keep the wait below the last MFMA issue
+        wait_vmcnt<0>();   // this wave's share of chunk c+1 (in flight during the compute above)
     }
 
     // ---- epilogue: normalise and store O (row = query l32, channels db*32 + (j/4)*8 + 4*half + j%4) ----
@@ -269,7 +307,9 @@ hipError_t launch_t(const AttnArgs& a, hipStream_t s) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma<NQ>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_attn_mfma<NQ>), dim3(a.Sb, a.td.H, a.td.B), dim3(Cfg<NQ>::kThreads), kLdsBytes, s, a);
+    const int total = a.Sb * a.td.H * a.td.B;
+    const int grid = (total + 7) / 8 * 8;          // every XCD gets the same number of slots
+    hipLaunchKernelGGL((k_attn_mfma<NQ>), dim3(grid), dim3(Cfg<NQ>::kThreads), kLdsBytes, s, a);
     return hipGetLastError();
 }
 
