@@ -122,6 +122,8 @@ def main():
     ap.add_argument("--config", default="cfg4")
     ap.add_argument("--heads", type=int, default=0, help="use only the first H heads (0 = the workload's own count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run three plain 1 GiB device copies (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (the path shards by head with no exchange; see DESIGN.md); "
@@ -134,6 +136,14 @@ def main():
     from workloads import CONFIGS
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "3 x copy of 1 GiB (reads 1048576 KiB, writes 1048576 KiB per copy)"}))
+        return
     wl = CONFIGS[args.config]
     H = args.heads or wl.H
     dev = "cuda:0"

@@ -139,11 +139,13 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) kf[mb][ks] = *(lds_v8)(uintptr_t)(rd.k_addr[ks] + kK + mb * 32 * kRowBytes);
+        __builtin_amdgcn_sched_barrier(0);   // all sixteen K reads in flight before the first MFMA waits
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][ks], qf[ks], s[mb], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
     // ---- V^T fragments: issued now so that they land while the softmax runs ----
     v8bf vf[2][2][4];
 #pragma unroll
