@@ -76,7 +76,7 @@ def read_traffic(kernel_tag):
         return None
 
 
-def cpu_baseline(wl, host_heads, ratio, kept_blocks_total, H, budget_s=20.0):
+def cpu_baseline(wl, host_heads, ratio, kept_blocks_total, H, budget_s=15.0):
     """Time the CPU oracle: scores + geometry + selection in full, attention on a sample of query blocks."""
     import numpy as np
     import torch
@@ -84,7 +84,6 @@ def cpu_baseline(wl, host_heads, ratio, kept_blocks_total, H, budget_s=20.0):
     f64 = lambda t: t.to(torch.float64).numpy()
     Q = np.stack([f64(host_heads[h][0]) for h in (0, 1)])[None]
     K = np.stack([f64(host_heads[h][1]) for h in (0, 1)])[None]
-    V0 = f64(host_heads[0][2])
     t0 = time.perf_counter()
     sc = o.block_scores(Q, K, wl.Bs, 2)
     tab = o.frame_table(wl.Nf, wl.Nt, wl.Bs, 1.0, wl.lam)
@@ -92,14 +91,17 @@ def cpu_baseline(wl, host_heads, ratio, kept_blocks_total, H, budget_s=20.0):
     rp, ci = o.build_mask(sc.astype(np.float32), cls, "static", ratio)[0][0]
     t_front = time.perf_counter() - t0
     rng = np.random.default_rng(7)
-    order = rng.permutation(wl.Sb)
     done_blocks, rows, t_attn = 0, 0, 0.0
-    for qb in order:
-        t1 = time.perf_counter()
-        o.masked_attention(Q[0, 0], K[0, 0], V0, rp, ci, wl.Bs, rows=[int(qb)])
-        t_attn += time.perf_counter() - t1
-        done_blocks += int(rp[qb + 1] - rp[qb])
-        rows += 1
+    for hd in (0, 1):
+        Vh = f64(host_heads[hd][2])
+        for qb in rng.permutation(wl.Sb):
+            t1 = time.perf_counter()
+            o.masked_attention(Q[0, hd], K[0, hd], Vh, rp, ci, wl.Bs, rows=[int(qb)])
+            t_attn += time.perf_counter() - t1
+            done_blocks += int(rp[qb + 1] - rp[qb])
+            rows += 1
+            if t_attn > budget_s:
+                break
         if t_attn > budget_s:
             break
     est_ms = (t_front + t_attn * (kept_blocks_total * H / max(1, done_blocks))) * 1e3
@@ -110,7 +112,7 @@ def cpu_baseline(wl, host_heads, ratio, kept_blocks_total, H, budget_s=20.0):
         cores = os.cpu_count() or 1
     return {"value": est_ms, "unit": "ms per attention call (extrapolated)", "cores": int(cores), "kind": "oracle",
             "sample": (f"block scores, geometry and selection in full ({t_front:.2f} s); fp64 masked attention on {rows} "
-                       f"random query blocks of head 0 ({done_blocks} kept key blocks, {t_attn:.2f} s) scaled by "
+                       f"query-block rows of heads 0-1 ({done_blocks} kept key blocks, {t_attn:.2f} s) scaled by "
                        f"kept blocks x heads = {kept_blocks_total * H}")}
 
 
@@ -236,6 +238,36 @@ def main():
                      "traffic": read_traffic(f"k_attn_mfma_{args.config}"),
                      "flop_per_launch": flop, "avg_launch_ms": round(ms_attn, 4)},
     }
+    # The scoring and mask stages are HBM/latency bound; with fused-head scoring (2 of 40 heads) they move only a few
+    # MB, so their bandwidth is shown on the per-head variant (head_fuse = 0: every head scored, one mask per head).
+    def timed(fn, iters=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+    ph = dr.MaskParams(head_fuse=0)
+    sc_h = torch.empty((wl.B, H, Sb, Sb), dtype=torch.float32, device=dev)
+    rp_h = torch.empty((wl.B, H, Sb + 1), dtype=torch.int32, device=dev)
+    ci_h = torch.empty((wl.B, H, cap), dtype=torch.int32, device=dev)
+    nz_h = torch.empty((wl.B, H), dtype=torch.int64, device=dev)
+    ms_sc = timed(lambda: dr.dr_block_scores(ctx, shape, Q, K, 0, sc_h))
+    ms_mk = timed(lambda: dr.dr_build_mask(ctx, shape, mode, par, wl.lam, ph, sc_h, rp_h, ci_h, cap, nz_h))
+    es = 2 if wl.dtype == "bf16" else 4
+    bytes_sc = 2.0 * wl.B * H * wl.N * wl.d * es + 4.0 * wl.B * H * Sb * Sb
+    bytes_mk = wl.B * H * (4.0 * Sb * Sb + Sb * Sb + 4.0 * (Sb + 1)) + 4.0 * float(nz_h.sum().item())
+    result["hbm_stages_per_head_variant"] = {
+        "block_scores": {"ms": round(ms_sc, 4), "algorithmic_bytes": bytes_sc,
+                         "GBps": round(bytes_sc / ms_sc / 1e6, 1), "frac_of_8TBps": round(bytes_sc / ms_sc / 1e6 / PEAK_HBM_GBS, 4)},
+        "build_mask": {"ms": round(ms_mk, 4), "algorithmic_bytes": bytes_mk,
+                       "GBps": round(bytes_mk / ms_mk / 1e6, 1), "frac_of_8TBps": round(bytes_mk / ms_mk / 1e6 / PEAK_HBM_GBS, 4)},
+    }
+    del sc_h, rp_h, ci_h, nz_h
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         result["cpu_baseline"] = cpu_baseline(wl, host_heads, par, n_kept, H)
