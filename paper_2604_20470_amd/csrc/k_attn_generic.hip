@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_generic(AttnArgs a) {
     for (int i = 0; i < DC; ++i) o[i] = 0.f;
 
     for (int it = beg; it < end; ++it) {
-        const int kb = ci[it];
+        const int kb = min(max(ci[it], 0), a.Sb - 1);   // clamped: a malformed list cannot address outside K/V
         const int k_blk0 = kb * a.Bs, k_blk1 = min(N, k_blk0 + a.Bs);
         for (int k0 = k_blk0; k0 < k_blk1; k0 += kChunk) {
             const int nk = min(kChunk, k_blk1 - k0);

@@ -221,3 +221,48 @@ def test_bad_arguments_are_rejected_on_the_host():
         dr.dr_sparse_attn_fwd(run.ctx, run.shape, run.Q, run.K, run.V, None, None, 1, 0, run.Q)
     # the context still works after errors
     run.build_mask(s, "static", 0.5)
+
+
+def test_strided_layout_batch_and_per_head_masks_on_the_mfma_path():
+    """[B, N, H, d] storage viewed as [B, H, N, d] (stride_n = H*d), B = 2, one mask per head, bf16/d=128/Bs=128."""
+    wl = tiny_case("ragged128", B=2, index=16)
+    run = GpuRun(wl, params=dr.MaskParams(head_fuse=0))
+    for name in ("Q", "K", "V"):
+        t = getattr(run, name)
+        strided = t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)      # same values, N-major storage
+        assert strided.stride(2) == wl.H * wl.d and strided.stride(1) == wl.d
+        setattr(run, name, strided)
+    run.shape = dr.shape_of(run.Q, wl.Nf, wl.Hg, wl.Wg, wl.Bs)
+    scores = run.block_scores()
+    want = o.block_scores(to_f64(run.Qc), to_f64(run.Kc), wl.Bs, 0)
+    assert score_error(scores, want) <= SCORE_TOL
+    cls = oracle_class_map(wl)
+    for mode, par in (("static", 0.3), ("dynamic", 0.9)):
+        rowptr, colidx, nnz, cap = run.build_mask(scores, mode, par)
+        assert_masks_equal(rowptr, colidx, nnz, oracle_masks_from(scores, cls, mode, par))
+        O = torch.full_like(run.Q, float("nan"))
+        dr.dr_sparse_attn_fwd(run.ctx, run.shape, run.Q, run.K, run.V, rowptr, colidx, wl.H, cap, O)
+        torch.cuda.synchronize()
+        rp, ci = rowptr.cpu().numpy(), colidx.cpu().numpy()
+        worst = 0.0
+        for b in range(wl.B):
+            for h in range(wl.H):
+                ref = o.masked_attention(to_f64(run.Qc[b, h]), to_f64(run.Kc[b, h]), to_f64(run.Vc[b, h]),
+                                         rp[b, h].astype(np.int64), ci[b, h, :rp[b, h, -1]].astype(np.int64), wl.Bs)
+                for qb, blk in ref.items():
+                    got = to_f64(O[b, h, qb * wl.Bs: qb * wl.Bs + blk.shape[0]])
+                    worst = max(worst, float(np.abs(got - blk).max()))
+        assert worst <= ATTN_TOL["bf16"], worst
+
+
+def test_key_block_list_with_out_of_range_entries_is_clamped_not_followed():
+    """Indices outside [0, Sb) are clamped by the kernels (memory safety); values are then those of the clamped list."""
+    wl = tiny_case("ragged128")
+    run = GpuRun(wl)
+    Sb = wl.Sb
+    rowptr = torch.arange(0, 2 * Sb + 1, 2, dtype=torch.int32, device="cuda").view(1, 1, -1).contiguous()
+    bad = torch.tensor([-5, Sb + 7] * Sb, dtype=torch.int32, device="cuda").view(1, 1, -1)
+    good = torch.tensor([0, Sb - 1] * Sb, dtype=torch.int32, device="cuda").view(1, 1, -1)
+    O_bad = run.attention(rowptr, bad, 2 * Sb)
+    O_good = run.attention(rowptr, good, 2 * Sb)
+    assert torch.equal(O_bad, O_good)
