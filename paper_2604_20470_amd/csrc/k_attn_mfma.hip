@@ -111,7 +111,8 @@ __device__ __forceinline__ float max_across_halves(float x) {
 
 struct State {
     v16f o[4];        // O^T accumulators: channel block db, value j -> channel db*32 + (j/4)*8 + 4*half + j%4
-    float m_ref;      // exponent reference (raw logit units), -inf before the first chunk
+    v16f cinit;       // -m_ref in all sixteen values: the C operand that starts every logit accumulation
+    float m_ref;      // exponent reference of this lane's query column, in log2 units (0 before the first chunk)
     float l_part;     // this lane's share of the normaliser
 };
 
@@ -121,18 +122,18 @@ struct ReadPlan {
 };
 
 template <int STAGE>
-__device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[8], State& st, float cs, int valid,
-                                           int half) {
+__device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[8], State& st, bool& first,
+                                           int valid, int half) {
     typedef __attribute__((address_space(3))) const v8bf* lds_v8;
     typedef __attribute__((address_space(3))) v4s* lds_v4;
     constexpr uint32_t kK = STAGE * kStageBytes, kV = STAGE * kStageBytes + kTileBytes;
 
     // ---- S^T = K Q^T : [64 keys x 32 queries], two independent accumulator chains ----
+    // Q is pre-scaled by log2(e)/sqrt(d) and the accumulation starts from -m_ref, so the MFMA output is directly
+    // the exponent of 2: no per-element scale or subtract is left for the vector ALU.
     v16f s[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) s[mb][j] = 0.f;
+    s[0] = st.cinit;
+    s[1] = st.cinit;
     {
         v8bf kf[2][8];
 #pragma unroll
@@ -177,17 +178,26 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
 #pragma unroll
         for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[mb][j]);
     mx = max_across_halves(mx);                         // finite: every chunk holds at least one valid key
-    if (__any((mx - st.m_ref) * cs > kRescaleThreshold)) {   // also true on the first chunk (m_ref = -inf)
-        const float m_new = fmaxf(st.m_ref, mx);
-        const float alpha = __builtin_amdgcn_exp2f((st.m_ref - m_new) * cs);
-        st.m_ref = m_new;
+    // mx is relative to the reference.  Move the reference (and rescale what was accumulated with the old one) only
+    // when a chunk exceeds it by more than the threshold, or on the first chunk, where it is set to the maximum
+    // whatever its sign.
+    if (first || __any(mx > kRescaleThreshold)) {
+        const float delta = first ? mx : fmaxf(mx, 0.f);
+        const float alpha = __builtin_amdgcn_exp2f(-delta);
+        st.m_ref += delta;
         st.l_part *= alpha;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) st.cinit[j] -= delta;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s[mb][j] -= delta;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int j = 0; j < 16; ++j) st.o[db][j] *= alpha;
+        first = false;
     }
-    const float mneg = -st.m_ref * cs;
     v8bf pf[2][2];
     v2bf ones;
     ones[0] = (__bf16)1.0f;
@@ -199,8 +209,8 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
 #pragma unroll
             for (int i = 0; i < 8; i += 2) {
                 v2bf pk;
-                pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[mb][t * 8 + i], cs, mneg));
-                pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[mb][t * 8 + i + 1], cs, mneg));
+                pk[0] = (__bf16)__builtin_amdgcn_exp2f(s[mb][t * 8 + i]);
+                pk[1] = (__bf16)__builtin_amdgcn_exp2f(s[mb][t * 8 + i + 1]);
                 st.l_part = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, st.l_part, false);
                 pf[mb][t][i] = pk[0];
                 pf[mb][t][i + 1] = pk[1];
@@ -245,6 +255,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int beg = __builtin_amdgcn_readfirstlane(rp[qb]);
     const int end = __builtin_amdgcn_readfirstlane(rp[qb + 1]);
 
+    const float cs = 1.4426950408889634f / sqrtf((float)kD);   // log2(e) / sqrt(d)
     // Q^T fragments (B operand of S^T = K Q^T): lane holds query l32, channels ks*16 + 8*half .. +7
     const int q_wave0 = qb * kBs + wave * 32;
     v8bf qf[8];
@@ -252,7 +263,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int qrow = min(q_wave0 + l32, N - 1);
         const char* src = Qh + (int64_t)qrow * row_bytes + half * 16;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const v8bf*>(src + ks * 32);
+        for (int ks = 0; ks < 8; ++ks) {
+            const v8bf raw = *reinterpret_cast<const v8bf*>(src + ks * 32);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qf[ks][i] = (__bf16)((float)raw[i] * cs);     // exponent scale folded into Q
+        }
     }
 
     const uint32_t lds0 = lds_addr(smem);
@@ -278,13 +293,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
 
     State st;
-    st.m_ref = -INFINITY;
+    st.m_ref = 0.f;
     st.l_part = 0.f;
+    bool first = true;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) st.cinit[j] = 0.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int j = 0; j < 16; ++j) st.o[db][j] = 0.f;
-    const float cs = 1.4426950408889634f / sqrtf((float)kD);   // log2(e) / sqrt(d)
 
     // The row's key-block list is walked through a 64-entry register window (lane i holds entry base + i):
     // the per-block index comes from v_readlane, so no memory access sits on the loop's critical path.
@@ -313,14 +330,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int n_chunks = (kb == a.Sb - 1) ? last_blk_chunks : 2;
         DR_BARRIER();
         if (n_chunks == 2) issue_chunk<1>(lp, Kh, Vh, key0 + kChunkKeys, N - 1);
-        chunk_body<0>(rd, qf, st, cs, N - key0, half);
+        chunk_body<0>(rd, qf, st, first, N - key0, half);
         DR_WAIT_VMCNT0();
         if (((blk + 1) & 63) == 0 && blk + 1 < n_blocks) win = load_window(blk + 1);
         kb_next = (blk + 1 < n_blocks) ? entry(win, blk + 1) : -1;
         if (n_chunks == 2) {
             DR_BARRIER();
             if (kb_next >= 0) issue_chunk<0>(lp, Kh, Vh, kb_next * kBs, N - 1);
-            chunk_body<1>(rd, qf, st, cs, N - key0 - kChunkKeys, half);
+            chunk_body<1>(rd, qf, st, first, N - key0 - kChunkKeys, half);
             DR_WAIT_VMCNT0();
         } else if (kb_next >= 0) {   // only for a list that is not ascending: nothing was prefetched, load serially
             DR_BARRIER();
@@ -347,7 +364,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
         if (a.lse && half == 0)
             a.lse[((int64_t)b * a.td.H + h) * N + qrow] =
-                (l > 0.f) ? st.m_ref * (1.0f / sqrtf((float)kD)) + logf(l) : -INFINITY;
+                (l > 0.f) ? st.m_ref * 0.6931471805599453f + logf(l) : -INFINITY;
     }
 }
 

@@ -139,7 +139,9 @@ def _attention_check(run, rowptr, colidx, cap, heads_rows, tol):
             assert np.isfinite(got).all(), (b, hi, qb)
             worst = max(worst, float(np.abs(got - blk).max()))
             gl = to_f64(lse[b, hi, r0:r0 + blk.shape[0]])
-            assert np.abs(gl - want_lse[qb]).max() <= (1e-4 if wl.dtype == "f32" else 2e-2), (b, hi, qb)
+            # log-sum-exp (auxiliary output): on the bf16 path Q is pre-multiplied by log2(e)/sqrt(d) and re-rounded
+            # to bf16, so a logit s carries an error of up to |s| * 2^-9 (about 0.03 at |s| ~ 14 in these workloads)
+            assert np.abs(gl - want_lse[qb]).max() <= (1e-4 if wl.dtype == "f32" else 5e-2), (b, hi, qb)
     assert worst <= tol, worst
     return worst
 
