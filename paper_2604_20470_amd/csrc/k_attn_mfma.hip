@@ -23,11 +23,15 @@
 // All LDS read addresses are (per-lane constant) + (compile-time immediate): the chunk loop is
 // unrolled over the two stages, and the swizzles are folded into twelve per-lane base registers.
 //
-// The running maximum used as the exponent reference is only raised when a chunk's maximum
-// exceeds it by more than 8 (in log2 units): softmax is invariant to the reference, P stays
-// below 2^8, and the rescale of the 64 output accumulators becomes rare.  The normaliser is
-// the sum of the bf16-rounded probabilities (v_dot2c_f32_bf16), i.e. exactly of what the
-// second product multiplies.
+// Softmax.  Q is pre-multiplied by log2(e)/sqrt(d) and every logit accumulation starts from -m_ref, so
+// the first product delivers the exponent of 2 directly.  The exponent reference m_ref of a query is set
+// to the row maximum of the first chunk and afterwards moved only when needed: softmax is invariant to
+// the reference, and fp32 / bf16 share one exponent range, so a stale reference costs no accuracy as
+// long as nothing overflows.  The guard is the chunk's own contribution to the normaliser (a lane's 32
+// probabilities, summed with v_dot2c_f32_bf16 from the bf16-rounded values, i.e. exactly what the second
+// product multiplies): while it stays below 2^10 no probability exceeds 2^10; otherwise the row maximum
+// is formed, the reference is raised to it, the 64 output accumulators are rescaled and the chunk's
+// exponentials are redone.  The steady state therefore has no maximum reduction at all.
 #include "dr_internal.h"
 
 namespace dr {
@@ -46,7 +50,7 @@ constexpr int kRowBytes = kD * 2;                    // 256
 constexpr int kTileBytes = kChunkKeys * kRowBytes;   // 16 KB per operand per stage
 constexpr int kStageBytes = 2 * kTileBytes;          // K then V
 constexpr int kLdsBytes = 2 * kStageBytes;           // two stages: 64 KB
-constexpr float kRescaleThreshold = 8.0f;            // log2 units
+constexpr float kSumLimit = 1024.0f;                 // a lane's 32 probabilities of a chunk may sum to at most this
 
 // The barrier carries no memory fence on purpose: a fence would drain the prefetch of the next
 // chunk.  Ordering of the direct-to-LDS loads is enforced by the explicit vmcnt waits.
@@ -121,9 +125,9 @@ struct ReadPlan {
     uint32_t v_addr[4];   // LDS address for channel block db (stage 0, mb 0, st 0, low half of the 8 keys)
 };
 
-template <int STAGE>
+template <int STAGE, class F>
 __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[8], State& st, bool& first,
-                                           int valid, int half) {
+                                           int valid, int half, F&& issue) {
     typedef __attribute__((address_space(3))) const v8bf* lds_v8;
     typedef __attribute__((address_space(3))) v4s* lds_v4;
     constexpr uint32_t kK = STAGE * kStageBytes, kV = STAGE * kStageBytes + kTileBytes;
@@ -141,6 +145,8 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) kf[mb][ks] = *(lds_v8)(uintptr_t)(rd.k_addr[ks] + kK + mb * 32 * kRowBytes);
         __builtin_amdgcn_sched_barrier(0);   // all sixteen K reads in flight before the first MFMA waits
+        issue();
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
@@ -172,16 +178,38 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
     }
 
     // ---- online softmax, per query column ----
-    float mx = -INFINITY;
+    // The exponentials are taken against the current reference straight away; the chunk's share of the normaliser
+    // doubles as the overflow guard (it bounds every probability of the lane), so the row maximum is only formed
+    // on the rare path that moves the reference (and on the first chunk, where no reference exists yet).
+    v8bf pf[2][2];
+    v2bf ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
+    auto exps = [&](float& lsum) {
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[mb][j]);
-    mx = max_across_halves(mx);                         // finite: every chunk holds at least one valid key
-    // mx is relative to the reference.  Move the reference (and rescale what was accumulated with the old one) only
-    // when a chunk exceeds it by more than the threshold, or on the first chunk, where it is set to the maximum
-    // whatever its sign.
-    if (first || __any(mx > kRescaleThreshold)) {
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) {
+                    v2bf pk;
+                    pk[0] = (__bf16)__builtin_amdgcn_exp2f(s[mb][t * 8 + i]);
+                    pk[1] = (__bf16)__builtin_amdgcn_exp2f(s[mb][t * 8 + i + 1]);
+                    lsum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lsum, false);
+                    pf[mb][t][i] = pk[0];
+                    pf[mb][t][i + 1] = pk[1];
+                }
+            }
+    };
+    float lc = 0.f;
+    if (!first) exps(lc);
+    if (first || __any(!(lc <= kSumLimit))) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[mb][j]);
+        mx = max_across_halves(mx);                         // finite: every chunk holds at least one valid key
         const float delta = first ? mx : fmaxf(mx, 0.f);
         const float alpha = __builtin_amdgcn_exp2f(-delta);
         st.m_ref += delta;
@@ -197,28 +225,12 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
 #pragma unroll
             for (int j = 0; j < 16; ++j) st.o[db][j] *= alpha;
         first = false;
+        lc = 0.f;
+        exps(lc);
     }
-    v8bf pf[2][2];
-    v2bf ones;
-    ones[0] = (__bf16)1.0f;
-    ones[1] = (__bf16)1.0f;
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-#pragma unroll
-            for (int i = 0; i < 8; i += 2) {
-                v2bf pk;
-                pk[0] = (__bf16)__builtin_amdgcn_exp2f(s[mb][t * 8 + i]);
-                pk[1] = (__bf16)__builtin_amdgcn_exp2f(s[mb][t * 8 + i + 1]);
-                st.l_part = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, st.l_part, false);
-                pf[mb][t][i] = pk[0];
-                pf[mb][t][i + 1] = pk[1];
-            }
-        }
+    st.l_part += lc;
 
     // ---- O^T += V^T P^T ----
-    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -329,15 +341,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int key0 = kb * kBs;
         const int n_chunks = (kb == a.Sb - 1) ? last_blk_chunks : 2;
         DR_BARRIER();
-        if (n_chunks == 2) issue_chunk<1>(lp, Kh, Vh, key0 + kChunkKeys, N - 1);
-        chunk_body<0>(rd, qf, st, first, N - key0, half);
+        chunk_body<0>(rd, qf, st, first, N - key0, half, [&]() { if (n_chunks == 2) issue_chunk<1>(lp, Kh, Vh, key0 + kChunkKeys, N - 1); });
         DR_WAIT_VMCNT0();
         if (((blk + 1) & 63) == 0 && blk + 1 < n_blocks) win = load_window(blk + 1);
         kb_next = (blk + 1 < n_blocks) ? entry(win, blk + 1) : -1;
         if (n_chunks == 2) {
             DR_BARRIER();
-            if (kb_next >= 0) issue_chunk<0>(lp, Kh, Vh, kb_next * kBs, N - 1);
-            chunk_body<1>(rd, qf, st, first, N - key0 - kChunkKeys, half);
+            chunk_body<1>(rd, qf, st, first, N - key0 - kChunkKeys, half, [&]() { if (kb_next >= 0) issue_chunk<0>(lp, Kh, Vh, kb_next * kBs, N - 1); });
             DR_WAIT_VMCNT0();
         } else if (kb_next >= 0) {   // only for a list that is not ascending: nothing was prefetched, load serially
             DR_BARRIER();
