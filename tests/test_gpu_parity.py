@@ -140,7 +140,7 @@ def _attention_check(run, rowptr, colidx, cap, heads_rows, tol):
             worst = max(worst, float(np.abs(got - blk).max()))
             gl = to_f64(lse[b, hi, r0:r0 + blk.shape[0]])
             # log-sum-exp (auxiliary output): on the bf16 path Q is pre-multiplied by log2(e)/sqrt(d) and re-rounded
-            # to bf16, so a logit s carries an error of up to |s| * 2^-9 (about 0.03 at |s| ~ 14 in these workloads)
+            # to bf16, so a logit s carries an error of up to 2^-8 * sum_k |q_k k_k| / sqrt(d) (a few 1e-2 at the logit magnitudes of these workloads)
             assert np.abs(gl - want_lse[qb]).max() <= (1e-4 if wl.dtype == "f32" else 5e-2), (b, hi, qb)
     assert worst <= tol, worst
     return worst
@@ -268,3 +268,49 @@ def test_key_block_list_with_out_of_range_entries_is_clamped_not_followed():
     O_bad = run.attention(rowptr, bad, 2 * Sb)
     O_good = run.attention(rowptr, good, 2 * Sb)
     assert torch.equal(O_bad, O_good)
+
+
+def _q_value_that_survives_prescaling(d):
+    """A bf16 value q0 in [4, 16) for which q0 * log2(e)/sqrt(d) is (almost) a bf16 number again."""
+    cs = np.float32(1.4426950408889634) / np.sqrt(np.float32(d))
+    cand = torch.cat([torch.arange(4, 8, 1 / 32), torch.arange(8, 16, 1 / 16)]).to(torch.bfloat16).float()
+    prod = cand * float(cs)
+    err = ((prod.to(torch.bfloat16).float() - prod).abs() / prod)
+    i = int(err.argmin())
+    assert float(err[i]) < 2.0 ** -13
+    return float(cand[i])
+
+
+@pytest.mark.parametrize("step,order", [(1.0, "ascending"), (1.0, "descending"), (32.0, "ascending"), (32.0, "descending")])
+def test_exponent_reference_moves_and_survives_overflow(step, order):
+    """Logits that drift by a fixed amount per key block (about `step` * 0.13 * q0 in log2 units, through a constant
+    channel q0 of Q against a per-block constant channel of K) force the MFMA path to move its exponent reference
+    repeatedly; with step = 32 the drift passes 2^128 relative to the first chunk, i.e. through the overflow of exp2.
+    The MFMA path rounds Q * log2(e)/sqrt(d) to bf16 once more (a logit error of up to |s| * 2^-8, random in sign
+    over the channels of ordinary data); this test is about the reference moves, so it keeps that rounding out of
+    the picture: q0 is chosen so that its pre-scaled value is a bf16 number, and V is constant inside a key block,
+    so the result depends on the block weights only."""
+    wl = tiny_case("ragged128")
+    run = GpuRun(wl)
+    Sb, Bs, N = wl.Sb, wl.Bs, wl.N
+    gen = torch.Generator().manual_seed(20470)
+    Qc, Kc = run.Qc.clone(), run.Kc.clone()
+    Vc = torch.empty_like(run.Vc)
+    Qc[..., 0] = _q_value_that_survives_prescaling(wl.d)
+    for j in range(Sb):
+        e = j if order == "ascending" else Sb - 1 - j
+        Kc[:, :, j * Bs:(j + 1) * Bs, 0] = step * e                    # exact in bf16
+        Vc[:, :, j * Bs:(j + 1) * Bs] = torch.randn(wl.B, wl.H, 1, wl.d, generator=gen).to(Vc.dtype)
+    run.Qc, run.Kc, run.Vc = Qc, Kc, Vc
+    run.Q, run.K, run.V = Qc.cuda(), Kc.cuda(), Vc.cuda()
+    rp, ci = o.full_csr(Sb)
+    rowptr = torch.from_numpy(rp.astype(np.int32)).view(1, 1, -1).contiguous().cuda()
+    colidx = torch.from_numpy(ci.astype(np.int32)).view(1, 1, -1).contiguous().cuda()
+    O = run.attention(rowptr, colidx, Sb * Sb)
+    assert torch.isfinite(O.float()).all()
+    worst = 0.0
+    for h in range(wl.H):
+        want = o.masked_attention(to_f64(Qc[0, h]), to_f64(Kc[0, h]), to_f64(Vc[0, h]), rp, ci, Bs)
+        for qb, blk in want.items():
+            worst = max(worst, float(np.abs(to_f64(O[0, h, qb * Bs: qb * Bs + blk.shape[0]]) - blk).max()))
+    assert worst <= ATTN_TOL["bf16"], worst
