@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+NOMINAL_MHZ = 2400.0
 PEAK_BF16_TFLOPS = 2500.0          # MI355X published dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
@@ -238,6 +239,27 @@ def main():
                      "traffic": read_traffic(f"k_attn_mfma_{args.config}"),
                      "flop_per_launch": flop, "avg_launch_ms": round(ms_attn, 4)},
     }
+    # Shader clock while the attention kernel runs (separate, untimed pass): a one-wave probe on a side stream
+    # spans ~60 % of a train of attention launches.  The MFMA peak is quoted at 2400 MHz; under this load the chip
+    # holds less, so the roofline fraction is also given against the peak at the measured clock.
+    def probe_clock(load_reps):
+        clk = torch.zeros(2, dtype=torch.int64, device=dev)
+        side = torch.cuda.Stream()
+        window_us = max(2000, int(0.6 * load_reps * ms_attn * 1e3)) if load_reps else 20000
+        torch.cuda.synchronize()
+        if load_reps:
+            dr.dr_sparse_attn_fwd(ctx, shape, Q, K, V, rowptr, colidx, 1, cap, O)
+        dr.dr_clock_probe(ctx, window_us, clk, stream=side)
+        for _ in range(load_reps):
+            dr.dr_sparse_attn_fwd(ctx, shape, Q, K, V, rowptr, colidx, 1, cap, O)
+        torch.cuda.synchronize()
+        ticks, ref = (int(x) for x in clk.tolist())
+        return 100.0 * ticks / max(ref, 1)
+    mhz_load = probe_clock(max(4, int(round(150.0 / ms_attn))))
+    mhz_idle = probe_clock(0)
+    result["clock"] = {"nominal_mhz": NOMINAL_MHZ, "under_attention_mhz": round(mhz_load, 1),
+                       "idle_probe_mhz": round(mhz_idle, 1),
+                       "roofline_frac_at_measured_clock": round(eff_tflops / (PEAK_BF16_TFLOPS * mhz_load / NOMINAL_MHZ), 4)}
     # The scoring and mask stages are HBM/latency bound; with fused-head scoring (2 of 40 heads) they move only a few
     # MB, so their bandwidth is shown on the per-head variant (head_fuse = 0: every head scored, one mask per head).
     def timed(fn, iters=20):

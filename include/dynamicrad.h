@@ -170,6 +170,17 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
                              const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads,
                              int64_t colidx_stride, void* O, float* lse, void* stream);
 
+/* Measurement aid (not a step of the method): average shader clock over a window.
+ * Enqueues a one-wavefront kernel on `stream` that polls the constant 100 MHz counter for
+ * `window_us` microseconds (1 .. 2 000 000) and then writes two uint64 to the device buffer
+ * `out`: out[0] = shader-clock ticks elapsed, out[1] = 100 MHz ticks elapsed, so that
+ * 100 * out[0] / out[1] is the mean shader clock in MHz over the window.  Run on a second
+ * stream beside the attention kernel it reports the clock the chip sustains under that load;
+ * the matrix-core peak the roofline is priced against assumes 2400 MHz.  Asynchronous; the
+ * caller synchronises `stream` before reading `out`.  Errors: DR_ERR_INVALID_ARG for a NULL
+ * pointer or a window out of range. */
+dr_status dr_clock_probe(dr_ctx* ctx, uint64_t window_us, uint64_t* out, void* stream);
+
 /* Library version string, e.g. "dynamicrad-gfx950 0.1". */
 const char* dr_version(void);
 

@@ -70,7 +70,8 @@ def load_library():
     lib.dr_block_scores.argtypes = [vp, shp, vp, vp, i32, vp, vp]
     lib.dr_build_mask.argtypes = [vp, shp, i32, f64, f64, mpp, vp, vp, vp, i64, vp, vp]
     lib.dr_sparse_attn_fwd.argtypes = [vp, shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
-    for name in ("dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
+    lib.dr_clock_probe.argtypes = [vp, C.c_uint64, vp, vp]
+    for name in ("dr_clock_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
                  "dr_sparse_attn_fwd"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -159,3 +160,8 @@ def dr_sparse_attn_fwd(ctx: Context, shape: Shape, Q, K, V, rowptr, colidx, mask
     ctx.check(ctx._lib.dr_sparse_attn_fwd(ctx._h, C.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(rowptr),
                                           _ptr(colidx), int(mask_heads), int(colidx_stride), _ptr(O), _ptr(lse),
                                           _stream(stream)))
+
+
+def dr_clock_probe(ctx: Context, window_us: int, out, stream=None):
+    """Enqueue the clock probe: `out` is a device int64 tensor of two entries (shader ticks, 100 MHz ticks)."""
+    ctx.check(ctx._lib.dr_clock_probe(ctx._h, int(window_us), _ptr(out), _stream(stream)))

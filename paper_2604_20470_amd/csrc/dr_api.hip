@@ -340,4 +340,13 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
     return DR_OK;
 }
 
+dr_status dr_clock_probe(dr_ctx* ctx, uint64_t window_us, uint64_t* out, void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    if (!out) return fail(ctx, DR_ERR_INVALID_ARG, "NULL output pointer");
+    if (window_us == 0 || window_us > 2000000) return fail(ctx, DR_ERR_INVALID_ARG, "window must be 1 us .. 2 s");
+    DeviceGuard g(ctx->device);
+    DR_HIP(ctx, launch_clock_probe(window_us * 100ull, reinterpret_cast<unsigned long long*>(out), (hipStream_t)stream));
+    return DR_OK;
+}
+
 }  // extern "C"

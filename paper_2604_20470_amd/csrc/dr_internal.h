@@ -71,4 +71,8 @@ hipError_t launch_attn_generic(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_supported(const AttnArgs& a);
 
+// ---- measurement aid ---------------------------------------------------------------------
+// out[0] = shader-clock ticks, out[1] = 100 MHz ticks elapsed over a window of window_ticks (100 MHz units).
+hipError_t launch_clock_probe(unsigned long long window_ticks, unsigned long long* out, hipStream_t s);
+
 }  // namespace dr

@@ -314,3 +314,15 @@ def test_exponent_reference_moves_and_survives_overflow(step, order):
         for qb, blk in want.items():
             worst = max(worst, float(np.abs(to_f64(O[0, h, qb * Bs: qb * Bs + blk.shape[0]]) - blk).max()))
     assert worst <= ATTN_TOL["bf16"], worst
+
+
+def test_clock_probe_reports_a_plausible_shader_clock():
+    ctx = dr.Context(0)
+    out = torch.zeros(2, dtype=torch.int64, device="cuda")
+    dr.dr_clock_probe(ctx, 5000, out)
+    torch.cuda.synchronize()
+    ticks, ref = out.tolist()
+    assert 5000 * 100 <= ref < 5000 * 100 * 3, ref            # the window, in 100 MHz ticks
+    assert 100.0 < 100.0 * ticks / ref < 3000.0               # MHz
+    with pytest.raises(dr.DRError):
+        dr.dr_clock_probe(ctx, 0, out)
