@@ -20,6 +20,13 @@ Stages, in the order of the method (paper sections in brackets):
   select_row        static-ratio top-k or dynamic cumulative-mass prefix on
                     one query-block row  [Eq. 8 with k = max(1, floor(n rho));
                     Eq. 11's keep-one fallback]
+  select_zscore     the paper's own dynamic-threshold rule restated per row:
+                    scores standardised inside each candidate set, thresholds
+                    tau_1 / tau_2 by decay state, keep-one fallback
+                    [score normalisation (Eq. 10), threshold selector (Eq. 11)]
+  select_uniform    the paper's own static-ratio rule restated per row: a
+                    seeded, score-free uniform sample of k blocks
+                    [Eq. 8 with k = max(1, floor(n rho)), "deterministic seed"]
   build_mask        all rows -> CSR (rowptr, colidx)  [Algorithm 1's output M_b]
   masked_attention  softmax over exactly the keys of the kept blocks
                     [Eqs. 12-13 with epsilon -> 0]
@@ -40,6 +47,17 @@ interpretation, listed again in the design notes):
     sample); dynamic mode keeps the shortest score-descending prefix whose
     softmax mass reaches tau of the total mass of the selectable blocks.
   * order of equal scores: lower key-block index first; -0.0 equals +0.0.
+  * z-score mode: the candidate set P(i, j) of a frame pair becomes, for a
+    query-block row, the selectable blocks that share the smallest frame
+    distance to the row AND lie on the same side of it (before / after): the
+    block-level image of "frame j = i - t" and "frame j = i + t".  Mean and
+    standard deviation are the population ones (divide by n), epsilon of
+    Eq. 10 is 1e-6, and a block is kept when z >= tau (Algorithm 1 writes >=).
+    All of it in fp64, sums taken one by one in ascending key-block order.
+  * uniform mode: every selectable block of a row gets the 32-bit key
+    fmix32(fmix32(seed ^ fmix32(qb)) + kb) (fmix32 = the finaliser of
+    MurmurHash3); the k blocks with the smallest keys are kept, equal keys by
+    lower index.  With two ratios NEAR and FAR blocks are sampled separately.
 
 Pins: tests/test_oracle_*.py check every function here against brute force,
 closed forms, hand-derived tables (tests/golden/) and invariants.  The paper's
@@ -306,12 +324,106 @@ def select_dynamic(scores_f32: np.ndarray, cls_row: np.ndarray, tau: float,
     return (kept, margin) if return_margin else kept
 
 
+def block_frame_gap(N: int, Nt: int, Bs: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Smallest frame distance between the tokens of each (query block, key block) and the side of the key block.
+
+    gap[qb, kb] = min |i - j| over frames i touched by qb and j touched by kb; side = +1 if the key block's
+    frames all come after the query block's, -1 if before, 0 if they overlap (gap 0).
+    """
+    Sb = -(-N // Bs)
+    starts = np.arange(Sb) * Bs
+    ends = np.minimum(N, starts + Bs)
+    f_lo, f_hi = starts // Nt, (ends - 1) // Nt
+    after = f_lo[None, :] - f_hi[:, None]        # key's first frame - query's last frame
+    before = f_lo[:, None] - f_hi[None, :]       # query's first frame - key's last frame
+    gap = np.maximum(0, np.maximum(after, before))
+    side = np.where(after > 0, 1, np.where(before > 0, -1, 0))
+    return gap.astype(np.int64), side.astype(np.int64)
+
+
+def select_zscore(scores_f32: np.ndarray, cls_row: np.ndarray, gap_row: np.ndarray, side_row: np.ndarray,
+                  tau_near: float, tau_far: float, eps: float = 1e-6) -> np.ndarray:
+    """Kept key blocks of one row under the paper's dynamic-threshold rule (Eqs. 10-11).
+
+    The selectable blocks of the row are split into candidate sets by (frame gap, side).  Inside a set:
+    mu = mean, sigma = population std, z = (s - mu) / (sigma + eps); keep z >= tau, with tau = tau_near for NEAR
+    blocks (decay length >= block size) and tau_far for FAR blocks; if nothing passes, keep the highest score
+    (lower index on ties).  Forced blocks (threshold -inf in Eq. 11) are always kept.
+    """
+    kept = list(np.flatnonzero(cls_row == CLASS_FORCED))
+    sel = np.flatnonzero((cls_row == CLASS_NEAR) | (cls_row == CLASS_FAR))
+    groups: Dict[Tuple[int, int], List[int]] = {}
+    for kb in sel:                                  # ascending key-block order
+        groups.setdefault((int(gap_row[kb]), int(side_row[kb])), []).append(int(kb))
+    for members in groups.values():
+        vals = [float(scores_f32[kb]) for kb in members]
+        n = len(vals)
+        total = 0.0
+        for x in vals:
+            total = total + x
+        mu = total / n
+        ssq = 0.0
+        for x in vals:
+            dlt = x - mu
+            ssq = ssq + dlt * dlt
+        sigma = math.sqrt(ssq / n)
+        passed = []
+        best = None
+        for kb, x in zip(members, vals):
+            tau = tau_near if cls_row[kb] == CLASS_NEAR else tau_far
+            if (x - mu) / (sigma + eps) >= tau:
+                passed.append(kb)
+            if best is None or x > best[0]:
+                best = (x, kb)
+        kept.extend(passed if passed else [best[1]])
+    return np.sort(np.asarray(kept, dtype=np.int64))
+
+
+def fmix32(x: int) -> int:
+    """Finaliser of MurmurHash3 (32-bit): a bijective integer mixer."""
+    x &= 0xFFFFFFFF
+    x ^= x >> 16
+    x = (x * 0x85EBCA6B) & 0xFFFFFFFF
+    x ^= x >> 13
+    x = (x * 0xC2B2AE35) & 0xFFFFFFFF
+    x ^= x >> 16
+    return x
+
+
+def sample_key(seed: int, qb: int, kb: int) -> int:
+    """Counter-based 32-bit key of block pair (qb, kb) under `seed`."""
+    return fmix32((fmix32((seed & 0xFFFFFFFF) ^ fmix32(qb)) + kb) & 0xFFFFFFFF)
+
+
+def select_uniform(qb: int, cls_row: np.ndarray, ratio: float, ratio_far: Optional[float], seed: int) -> np.ndarray:
+    """Kept key blocks of row qb under the paper's static-ratio rule: a seeded uniform sample of
+    k = max(1, floor(n rho)) selectable blocks (Eq. 8), scores not consulted."""
+    forced = np.flatnonzero(cls_row == CLASS_FORCED)
+    if ratio_far is None or ratio_far < 0:
+        groups = [(np.flatnonzero((cls_row == CLASS_NEAR) | (cls_row == CLASS_FAR)), ratio)]
+    else:
+        groups = [(np.flatnonzero(cls_row == CLASS_NEAR), ratio),
+                  (np.flatnonzero(cls_row == CLASS_FAR), ratio_far)]
+    kept = [forced]
+    for idx, rho in groups:
+        k = static_keep_count(len(idx), rho)
+        order = sorted(idx.tolist(), key=lambda kb: (sample_key(seed, qb, kb), kb))
+        kept.append(np.asarray(order[:k], dtype=np.int64))
+    return np.sort(np.concatenate(kept)).astype(np.int64)
+
+
 # --------------------------------------------------------------------------- #
 # stage (b4): whole mask as CSR
 # --------------------------------------------------------------------------- #
 def build_mask(scores_f32: np.ndarray, cls_map: np.ndarray, mode: str, ratio_or_tau: float,
-               ratio_far: Optional[float] = None) -> List[List[Tuple[np.ndarray, np.ndarray]]]:
-    """CSR (rowptr, colidx) per (batch, mask head).  scores_f32: [B, Hm, Sb, Sb] float32."""
+               ratio_far: Optional[float] = None, gap_side: Optional[Tuple[np.ndarray, np.ndarray]] = None,
+               tau_far: Optional[float] = None, seed: int = 0) -> List[List[Tuple[np.ndarray, np.ndarray]]]:
+    """CSR (rowptr, colidx) per (batch, mask head).  scores_f32: [B, Hm, Sb, Sb] float32.
+
+    mode "static" / "dynamic": the pooled-score top-k and cumulative-mass rules; "zscore": select_zscore with
+    tau_near = ratio_or_tau and tau_far (default: the same), needs gap_side = block_frame_gap(...);
+    "uniform": select_uniform with `seed` (scores are only used for their shape).
+    """
     scores_f32 = np.asarray(scores_f32)
     assert scores_f32.dtype == np.float32
     B, Hm, Sb, _ = scores_f32.shape
@@ -326,6 +438,11 @@ def build_mask(scores_f32: np.ndarray, cls_map: np.ndarray, mode: str, ratio_or_
                     kept = select_static(scores_f32[b, m, qb], cls_map[qb], ratio_or_tau, ratio_far)
                 elif mode == "dynamic":
                     kept = select_dynamic(scores_f32[b, m, qb], cls_map[qb], ratio_or_tau)
+                elif mode == "zscore":
+                    kept = select_zscore(scores_f32[b, m, qb], cls_map[qb], gap_side[0][qb], gap_side[1][qb],
+                                         ratio_or_tau, ratio_or_tau if tau_far is None else tau_far)
+                elif mode == "uniform":
+                    kept = select_uniform(qb, cls_map[qb], ratio_or_tau, ratio_far, seed)
                 else:
                     raise ValueError(mode)
                 cols.append(kept)
