@@ -290,6 +290,14 @@ def main():
                        "GBps": round(bytes_mk / ms_mk / 1e6, 1), "frac_of_8TBps": round(bytes_mk / ms_mk / 1e6 / PEAK_HBM_GBS, 4)},
     }
     del sc_h, rp_h, ci_h, nz_h
+    # build_mask alone in each selection rule (fused-head scores, one mask): latency-bound launches
+    pz = dr.MaskParams(head_fuse=wl.head_fuse, tau_far=0.8, seed=1)
+    result["build_mask_ms_by_rule"] = {
+        "static_topk": round(timed(lambda: dr.dr_build_mask(ctx, shape, dr.MODE_STATIC, 0.05, wl.lam, params, scores, rowptr, colidx, cap, nnz)), 4),
+        "cumulative_mass": round(timed(lambda: dr.dr_build_mask(ctx, shape, dr.MODE_DYNAMIC, 0.9, wl.lam, params, scores, rowptr, colidx, cap, nnz)), 4),
+        "zscore_threshold": round(timed(lambda: dr.dr_build_mask(ctx, shape, dr.MODE_ZSCORE, 0.3, wl.lam, pz, scores, rowptr, colidx, cap, nnz)), 4),
+        "uniform_sample": round(timed(lambda: dr.dr_build_mask(ctx, shape, dr.MODE_UNIFORM, 0.05, wl.lam, pz, None, rowptr, colidx, cap, nnz)), 4),
+    }
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         result["cpu_baseline"] = cpu_baseline(wl, host_heads, par, n_kept, H)

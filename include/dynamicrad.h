@@ -55,7 +55,11 @@ typedef enum { DR_F32 = 0, DR_BF16 = 1 } dr_dtype;
 
 typedef enum {
     DR_MODE_STATIC_RATIO = 0,      /* keep the top max(1, floor(n*rho)) selectable blocks of a row by score */
-    DR_MODE_DYNAMIC_THRESHOLD = 1  /* keep the shortest score-descending prefix holding >= tau of the softmax mass */
+    DR_MODE_DYNAMIC_THRESHOLD = 1, /* keep the shortest score-descending prefix holding >= tau of the softmax mass */
+    DR_MODE_ZSCORE_THRESHOLD = 2,  /* the paper's own dynamic rule: scores standardised per candidate set, kept when
+                                      z >= tau_1 (near) / tau_2 (far), keep-one fallback (Eqs. 10-11) */
+    DR_MODE_UNIFORM_RATIO = 3      /* the paper's own static rule: a seeded, score-free uniform sample of
+                                      max(1, floor(n*rho)) selectable blocks (Eq. 8) */
 } dr_mode;
 
 /* Problem shape.  Paper notation: Nf frames, Nt = Hg*Wg tokens per frame, S = N tokens, Bs block size. */
@@ -75,7 +79,10 @@ typedef struct {
     double ratio_far;    /* static mode: ratio for far-field blocks (decay length < Bs); < 0: same as ratio.  Default -1 */
     int32_t head_fuse;   /* Hf > 0: scores are the mean over heads 0..Hf-1, one mask per batch element;
                             0: one mask per head.  Default 2 (App. B, head-fusion proxy) */
-    int32_t reserved[7]; /* must be 0 */
+    int32_t has_tau_far; /* z-score mode: 1 = `tau_far` is the threshold of far-field blocks; 0 = same as near.  Default 0 */
+    double tau_far;      /* z-score mode: tau_2 of Eq. 11 (any real, -inf allowed) when has_tau_far = 1.  Default 0 */
+    uint32_t seed;       /* uniform mode: seed of the counter-based sample.  Default 0 */
+    int32_t reserved[3]; /* must be 0 */
 } dr_mask_params;
 
 /* Block classes written by dr_class_map. */
@@ -133,12 +140,27 @@ dr_status dr_block_scores(dr_ctx* ctx, const dr_shape* shape, const void* Q, con
  *   dynamic : e_j = exp(s_j - max s) in fp64, summed one by one in that order;
  *             the shortest prefix whose sum >= tau * (total sum); at least one
  *             (the keep-one fallback of Eq. 11 / Algorithm 1).
+ *   z-score : (Eqs. 10-11 at block level) the row's NEAR/FAR blocks are split into
+ *             candidate sets by (smallest frame distance to the query block, side
+ *             before/after it) -- the image of the paper's frame pair (i, j).  Per set, in
+ *             fp64 with sums taken one by one in ascending key-block order:
+ *             mu = mean, sigma = sqrt(mean (s - mu)^2), z = (s - mu) / (sigma + 1e-6);
+ *             a block is kept when z >= tau, tau = `ratio_or_tau` for NEAR blocks and
+ *             params->tau_far for FAR blocks (if has_tau_far); a set where nothing passes
+ *             keeps its highest score (lower index on ties).
+ *   uniform : (Eq. 8 as the paper words it) scores are not read (`scores` may be NULL);
+ *             every NEAR/FAR block gets the 32-bit key
+ *             fmix32(fmix32(seed ^ fmix32(qb)) + kb), fmix32 = MurmurHash3's finaliser;
+ *             the max(1, floor(n * ratio)) smallest keys are kept (ties by lower index);
+ *             with params->ratio_far >= 0 NEAR and FAR are sampled separately.  The mask
+ *             depends on the geometry and the seed only, so a caller can build it once.
  * Output is CSR per mask: rowptr[b, m, 0..Sb] (rowptr[..,0] = 0) and strictly
  * ascending key-block indices in colidx[b, m, rowptr[qb] .. rowptr[qb+1]).
  *   mode           dr_mode
- *   ratio_or_tau   ratio in (0, 1] or tau in (0, 1]
+ *   ratio_or_tau   ratio in (0, 1] (static, uniform), tau in (0, 1] (dynamic), or tau_1, any real (z-score)
  *   lambda         long-range factor of Eq. 4, > 0
- *   scores         device float32 [B, masks, Sb, Sb] (masks from params->head_fuse); must be finite
+ *   scores         device float32 [B, masks, Sb, Sb] (masks from params->head_fuse); must be finite;
+ *                  may be NULL in uniform mode
  *   rowptr         device int32 [B, masks, Sb + 1]
  *   colidx         device int32 [B, masks, colidx_capacity]
  *   colidx_capacity  entries available per mask; > 0

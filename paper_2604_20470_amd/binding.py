@@ -8,7 +8,7 @@ from typing import Optional, Tuple
 HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libdynamicrad.so"
 
-MODE_STATIC, MODE_DYNAMIC = 0, 1
+MODE_STATIC, MODE_DYNAMIC, MODE_ZSCORE, MODE_UNIFORM = 0, 1, 2, 3
 CLASS_NONE, CLASS_NEAR, CLASS_FAR, CLASS_FORCED = 0, 1, 2, 3
 _STATUS = {0: "DR_OK", 1: "DR_ERR_INVALID_ARG", 2: "DR_ERR_UNSUPPORTED", 3: "DR_ERR_CAPACITY", 4: "DR_ERR_HIP",
            5: "DR_ERR_NOMEM"}
@@ -34,10 +34,12 @@ class Shape(C.Structure):
 
 class MaskParams(C.Structure):
     _fields_ = [("gamma", C.c_double), ("theta_c", C.c_double), ("theta_m", C.c_double),
-                ("ratio_far", C.c_double), ("head_fuse", C.c_int32), ("reserved", C.c_int32 * 7)]
+                ("ratio_far", C.c_double), ("head_fuse", C.c_int32), ("has_tau_far", C.c_int32),
+                ("tau_far", C.c_double), ("seed", C.c_uint32), ("reserved", C.c_int32 * 3)]
 
-    def __init__(self, gamma=1.0, theta_c=0.15, theta_m=0.60, ratio_far=-1.0, head_fuse=2):
-        super().__init__(gamma, theta_c, theta_m, ratio_far, head_fuse)
+    def __init__(self, gamma=1.0, theta_c=0.15, theta_m=0.60, ratio_far=-1.0, head_fuse=2, tau_far=None, seed=0):
+        super().__init__(gamma, theta_c, theta_m, ratio_far, head_fuse, 0 if tau_far is None else 1,
+                         0.0 if tau_far is None else tau_far, seed)
 
 
 def lib_path() -> str:

@@ -65,7 +65,7 @@ struct DeviceGuard {
     }
 };
 
-const dr_mask_params kDefaults = {1.0, 0.15, 0.60, -1.0, 2, {0, 0, 0, 0, 0, 0, 0}};
+const dr_mask_params kDefaults = {1.0, 0.15, 0.60, -1.0, 2, 0, 0.0, 0u, {0, 0, 0}};
 
 dr_status grow(dr_ctx* ctx, void** p, size_t* have, size_t need) {
     if (*have >= need) return DR_OK;
@@ -118,7 +118,9 @@ dr_status check_params(dr_ctx* ctx, const dr_mask_params* p, double lambda) {
     if (p->ratio_far > 1.0 || p->ratio_far == 0.0 || std::isnan(p->ratio_far))
         return fail(ctx, DR_ERR_INVALID_ARG, "ratio_far must be < 0 (unused) or in (0,1]");
     if (p->head_fuse < 0) return fail(ctx, DR_ERR_INVALID_ARG, "head_fuse must be >= 0");
-    for (int i = 0; i < 7; ++i)
+    if (p->has_tau_far != 0 && p->has_tau_far != 1) return fail(ctx, DR_ERR_INVALID_ARG, "has_tau_far must be 0 or 1");
+    if (p->has_tau_far && std::isnan(p->tau_far)) return fail(ctx, DR_ERR_INVALID_ARG, "tau_far is NaN");
+    for (int i = 0; i < 3; ++i)
         if (p->reserved[i] != 0) return fail(ctx, DR_ERR_INVALID_ARG, "reserved fields must be 0");
     return DR_OK;
 }
@@ -283,12 +285,16 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
     if ((st = check_params(ctx, p, lambda)) != DR_OK) return st;
     if (shape->B <= 0 || shape->H <= 0) return fail(ctx, DR_ERR_INVALID_ARG, "non-positive B or H");
     if (shape->B > 65535 || shape->H > 65535) return fail(ctx, DR_ERR_UNSUPPORTED, "B or H too large for the launch grid");
-    if (mode != DR_MODE_STATIC_RATIO && mode != DR_MODE_DYNAMIC_THRESHOLD)
+    if (mode < DR_MODE_STATIC_RATIO || mode > DR_MODE_UNIFORM_RATIO)
         return fail(ctx, DR_ERR_INVALID_ARG, "unknown mode %d", mode);
-    if (!(ratio_or_tau > 0.0 && ratio_or_tau <= 1.0))
-        return fail(ctx, DR_ERR_INVALID_ARG, "%s must be in (0,1]", mode == DR_MODE_STATIC_RATIO ? "ratio" : "tau");
+    if (mode == DR_MODE_ZSCORE_THRESHOLD) {
+        if (std::isnan(ratio_or_tau)) return fail(ctx, DR_ERR_INVALID_ARG, "tau_1 is NaN");
+    } else if (!(ratio_or_tau > 0.0 && ratio_or_tau <= 1.0)) {
+        return fail(ctx, DR_ERR_INVALID_ARG, "%s must be in (0,1]", mode == DR_MODE_DYNAMIC_THRESHOLD ? "tau" : "ratio");
+    }
     if (p->head_fuse > shape->H) return fail(ctx, DR_ERR_INVALID_ARG, "head_fuse=%d > H", p->head_fuse);
-    if (!scores || !rowptr || !colidx || !nnz) return fail(ctx, DR_ERR_INVALID_ARG, "NULL output or scores pointer");
+    if ((!scores && mode != DR_MODE_UNIFORM_RATIO) || !rowptr || !colidx || !nnz)
+        return fail(ctx, DR_ERR_INVALID_ARG, "NULL output or scores pointer");
     if (colidx_capacity <= 0) return fail(ctx, DR_ERR_CAPACITY, "colidx_capacity must be > 0");
     DeviceGuard g(ctx->device);
     hipStream_t s = (hipStream_t)stream;
@@ -303,14 +309,21 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
     if ((st = grow(ctx, (void**)&ctx->counts, &ctx->count_bytes, rows * 4)) != DR_OK) return st;
     SelectArgs a{};
     a.mode = mode;
-    a.two_ratio = (mode == DR_MODE_STATIC_RATIO && p->ratio_far > 0.0) ? 1 : 0;
+    a.two_ratio = ((mode == DR_MODE_STATIC_RATIO || mode == DR_MODE_UNIFORM_RATIO) && p->ratio_far > 0.0) ? 1 : 0;
     a.ratio = ratio_or_tau;
     a.ratio_far = p->ratio_far;
     a.tau = ratio_or_tau;
     int cap = 1;
     while (cap < ctx->max_sel) cap <<= 1;
     a.sort_cap = cap;
-    DR_HIP(ctx, launch_select(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
+    a.tau_near = ratio_or_tau;
+    a.tau_far = p->has_tau_far ? p->tau_far : ratio_or_tau;
+    a.seed = p->seed;
+    a.N = shape->N; a.Nt = shape->Hg * shape->Wg; a.Nf = shape->Nf; a.Bs = shape->Bs;
+    if (mode == DR_MODE_ZSCORE_THRESHOLD)
+        DR_HIP(ctx, launch_select_zscore(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
+    else
+        DR_HIP(ctx, launch_select(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
     DR_HIP(ctx, launch_emit(ctx->keepbits, ctx->counts, shape->B, masks, Sb, rowptr, colidx, colidx_capacity, nnz, s));
     return DR_OK;
 }

@@ -41,14 +41,20 @@ hipError_t launch_scores(const float* pooled, int B, int Hs, int masks, int head
 hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* class_map, int32_t* row_sel,
                             unsigned long long* totals, hipStream_t s);
 struct SelectArgs {
-    int32_t mode;            // 0 static, 1 dynamic
-    int32_t two_ratio;       // static: rank NEAR and FAR separately
+    int32_t mode;            // dr_mode: 0 static top-k, 1 cumulative mass, 2 z-score thresholds, 3 seeded uniform sample
+    int32_t two_ratio;       // static / uniform: rank NEAR and FAR separately
     double ratio, ratio_far, tau;
+    double tau_near, tau_far;   // z-score mode (Eq. 11's tau_1, tau_2)
     int32_t sort_cap;        // power of two >= the largest selectable count of a row
+    uint32_t seed;           // uniform mode
+    int32_t N, Nt, Nf, Bs;   // geometry, for the candidate sets of the z-score mode
 };
 // keepbits[(b*masks+m)*Sb + qb][words], counts[(b*masks+m)*Sb + qb]
 hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
                          const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
+// z-score mode (paper Eqs. 10-11 at block level); same outputs as launch_select
+hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
+                                const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
 hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb,
                        int32_t* rowptr, int32_t* colidx, int64_t capacity, int64_t* nnz, hipStream_t s);
 

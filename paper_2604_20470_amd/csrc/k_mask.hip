@@ -7,6 +7,11 @@
 //                blocks into LDS as 64-bit sort keys, bitonic-sorts them, then takes the
 //                static top-k or the dynamic cumulative-mass prefix (paper Eq. 8 k rule;
 //                keep-one fallback of Eq. 11 / Algorithm 1).
+//                In the seeded uniform mode (Eq. 8 as worded in the paper) the sort key is a
+//                counter-based hash of (seed, query block, key block) instead of the score.
+//   k_select_zscore  the paper's dynamic rule (Eqs. 10-11) per row: lanes own candidate sets
+//                (frame distance, side), standardise the scores of a set in fp64 and keep
+//                z >= tau_1 / tau_2, with the keep-one fallback.
 //   k_emit       per row: offset = sum of the previous rows' counts, bit-expansion to
 //                ascending key-block indices.
 #include "dr_internal.h"
@@ -95,6 +100,35 @@ __device__ __forceinline__ float key_score(uint64_t key) {
 }
 __device__ __forceinline__ int key_block(uint64_t key) { return (int)(key & 0x7fffffffu); }
 
+// MurmurHash3's 32-bit finaliser; the sample key of block pair (qb, kb) under a seed
+__device__ __forceinline__ uint32_t fmix32(uint32_t x) {
+    x ^= x >> 16;
+    x *= 0x85EBCA6Bu;
+    x ^= x >> 13;
+    x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ uint64_t make_sample_key(uint32_t seed, int qb, int kb, bool far_bit) {
+    const uint32_t h = fmix32(fmix32(seed ^ fmix32((uint32_t)qb)) + (uint32_t)kb);
+    return ((uint64_t)(far_bit ? 1 : 0) << 63) | ((uint64_t)h << 31) | (uint64_t)(uint32_t)kb;
+}
+
+// keep bitmask of one row -> global memory, and the row's count
+__device__ __forceinline__ void store_row(const uint32_t* keep, int words, int64_t row, uint32_t* __restrict__ keepbits,
+                                          int32_t* __restrict__ counts, int* s_cnt) {
+    int c = 0;
+    for (int i = threadIdx.x; i < words; i += kThreads) {
+        const uint32_t wv = keep[i];
+        keepbits[row * words + i] = wv;
+        c += __popc(wv);
+    }
+    for (int off = 32; off > 0; off >>= 1) c += __shfl_down(c, off);
+    if (lane_id() == 0) atomicAdd(s_cnt, c);
+    __syncthreads();
+    if (threadIdx.x == 0) counts[row] = *s_cnt;
+}
+
 __device__ __forceinline__ int keep_count(int n, double ratio) {
     if (n == 0) return 0;
     const int k = (int)floor((double)n * ratio);
@@ -130,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
             const int pos = atomicAdd(&s_n, 1);
             const bool far_bit = a.two_ratio && c == 2;
             if (a.two_ratio && c == 1) atomicAdd(&s_near, 1);
-            keys[pos] = make_key(srow[kb], kb, far_bit);
+            keys[pos] = (a.mode == 3) ? make_sample_key(a.seed, qb, kb, far_bit) : make_key(srow[kb], kb, far_bit);
         }
     }
     __syncthreads();
@@ -153,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
                 __syncthreads();
             }
         }
-        if (a.mode == 0) {
+        if (a.mode != 1) {
             if (a.two_ratio) {
                 const int n_near = s_near;
                 const int k_near = keep_count(n_near, a.ratio), k_far = keep_count(n - n_near, a.ratio_far);
@@ -189,16 +223,73 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
         }
     }
     __syncthreads();
-    int c = 0;
-    for (int i = tid; i < words; i += kThreads) {
-        const uint32_t wv = keep[i];
-        keepbits[row * words + i] = wv;
-        c += __popc(wv);
-    }
-    for (int off = 32; off > 0; off >>= 1) c += __shfl_down(c, off);
-    if (lane_id() == 0) atomicAdd(&s_cnt, c);
+    store_row(keep, words, row, keepbits, counts, &s_cnt);
+}
+
+// grid: (Sb, masks, B).  LDS: keep[words] u32.  Thread g owns the candidate sets g, g + 256, ...; set id =
+// 2 * (frame gap) + (key block after the query block).  The three passes over a set run in ascending key-block
+// order, one addition at a time, with floating-point contraction off: the summation order and the absence of fused
+// multiply-adds are part of the definition the results are compared against.
+__global__ __launch_bounds__(kThreads) void k_select_zscore(const uint8_t* __restrict__ class_map,
+                                                            const float* __restrict__ scores, int masks, int Sb,
+                                                            SelectArgs a, uint32_t* __restrict__ keepbits,
+                                                            int32_t* __restrict__ counts) {
+#pragma clang fp contract(off)
+    extern __shared__ unsigned char smem[];
+    uint32_t* keep = reinterpret_cast<uint32_t*>(smem);
+    __shared__ int s_cnt;
+    const int qb = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int words = (Sb + 31) / 32;
+    const int64_t row = ((int64_t)b * masks + m) * Sb + qb;
+    const float* srow = scores + row * Sb;
+    const uint8_t* crow = class_map + (int64_t)qb * Sb;
+    for (int i = tid; i < words; i += kThreads) keep[i] = 0u;
+    if (tid == 0) s_cnt = 0;
     __syncthreads();
-    if (tid == 0) counts[row] = s_cnt;
+    for (int kb = tid; kb < Sb; kb += kThreads)
+        if (crow[kb] == 3) atomicOr(&keep[kb >> 5], 1u << (kb & 31));
+    const int r0 = qb * a.Bs, r1 = min(a.N, r0 + a.Bs);
+    const int i0 = r0 / a.Nt, i1 = (r1 - 1) / a.Nt;
+    for (int gid = 4 + tid; gid < 2 * a.Nf; gid += kThreads) {       // gaps 0 and 1 are the never-pruned zone
+        const int gap = gid >> 1;
+        const bool after = gid & 1;
+        const int f = after ? i1 + gap : i0 - gap;                   // the frame that realises the gap
+        if (f < 0 || f >= a.Nf) continue;
+        const int kb_lo = (int)(((int64_t)f * a.Nt) / a.Bs);
+        const int kb_hi = min(Sb - 1, (int)((((int64_t)f + 1) * a.Nt - 1) / a.Bs));
+        auto member = [&](int kb) {
+            const int c = crow[kb];
+            if (c != 1 && c != 2) return false;
+            const int c0 = kb * a.Bs, c1 = min(a.N, c0 + a.Bs);
+            const int j0 = c0 / a.Nt, j1 = (c1 - 1) / a.Nt;
+            return after ? (j0 - i1 == gap) : (i0 - j1 == gap);
+        };
+        int n = 0;
+        double sum = 0.0;
+        for (int kb = kb_lo; kb <= kb_hi; ++kb)
+            if (member(kb)) { sum = sum + (double)srow[kb]; ++n; }
+        if (n == 0) continue;
+        const double mu = sum / (double)n;
+        double ssq = 0.0;
+        for (int kb = kb_lo; kb <= kb_hi; ++kb)
+            if (member(kb)) { const double dlt = (double)srow[kb] - mu; const double sq = dlt * dlt; ssq = ssq + sq; }
+        const double denom = sqrt(ssq / (double)n) + 1e-6;
+        bool any = false;
+        int best_kb = -1;
+        float best_s = 0.f;
+        for (int kb = kb_lo; kb <= kb_hi; ++kb)
+            if (member(kb)) {
+                const float x = srow[kb];
+                const double z = ((double)x - mu) / denom;
+                const double tau = (crow[kb] == 1) ? a.tau_near : a.tau_far;
+                if (z >= tau) { any = true; atomicOr(&keep[kb >> 5], 1u << (kb & 31)); }
+                if (best_kb < 0 || x > best_s) { best_kb = kb; best_s = x; }
+            }
+        if (!any) atomicOr(&keep[best_kb >> 5], 1u << (best_kb & 31));
+    }
+    __syncthreads();
+    store_row(keep, words, row, keepbits, counts, &s_cnt);
 }
 
 // grid: (Sb, masks, B)
@@ -279,6 +370,14 @@ hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, i
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(k_select, dim3(Sb, masks, B), dim3(kThreads), lds, s, class_map, scores, masks, Sb, a,
+                       keepbits, counts);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
+                                const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s) {
+    const size_t lds = (size_t)((Sb + 31) / 32) * 4;
+    hipLaunchKernelGGL(k_select_zscore, dim3(Sb, masks, B), dim3(kThreads), lds, s, class_map, scores, masks, Sb, a,
                        keepbits, counts);
     return hipGetLastError();
 }

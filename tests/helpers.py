@@ -60,8 +60,9 @@ class GpuRun:
         rowptr = torch.full((B, M, self.Sb + 1), -7, dtype=torch.int32, device=self.device)
         colidx = torch.full((B * M * capacity + guard,), -7, dtype=torch.int32, device=self.device)
         nnz = torch.full((B, M), -7, dtype=torch.int64, device=self.device)
-        dr.dr_build_mask(self.ctx, self.shape, dr.MODE_STATIC if mode == "static" else dr.MODE_DYNAMIC, par, lam,
-                         self.params, scores, rowptr, colidx, capacity, nnz)
+        code = {"static": dr.MODE_STATIC, "dynamic": dr.MODE_DYNAMIC, "zscore": dr.MODE_ZSCORE,
+                "uniform": dr.MODE_UNIFORM}[mode]
+        dr.dr_build_mask(self.ctx, self.shape, code, par, lam, self.params, scores, rowptr, colidx, capacity, nnz)
         torch.cuda.synchronize()
         assert (colidx[B * M * capacity:] == -7).all(), "colidx guard overwritten"
         return rowptr, colidx[:B * M * capacity].view(B, M, capacity), nnz, capacity

@@ -1,0 +1,95 @@
+"""GPU parity for the paper's own selection rules at block level: standardised-score thresholds (Eqs. 10-11) and the
+seeded uniform sample (Eq. 8).  Masks are compared bit for bit with the oracle, which selects from the GPU's own fp32
+block scores."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_20470_amd as dr
+from oracle import dynamicrad_oracle as o
+from workloads import CONFIGS, tiny_case
+
+from helpers import GpuRun, assert_masks_equal, oracle_class_map
+
+pytestmark = pytest.mark.gpu
+
+CASES = [tiny_case("tiny8"), tiny_case("ragged"), tiny_case("ragged128"), CONFIGS["cfg2"]]
+
+
+def _ids(w):
+    return f"{w.name}-Bs{w.Bs}"
+
+
+@pytest.mark.parametrize("wl", CASES, ids=_ids)
+@pytest.mark.parametrize("head_fuse", [2, 0])
+def test_zscore_masks_bit_exact(wl, head_fuse):
+    gs = o.block_frame_gap(wl.N, wl.Nt, wl.Bs)
+    for gamma in (1.0, 3.0):                      # gamma = 3 gives both NEAR and FAR sets on the small cases
+        cls = oracle_class_map(wl, gamma=gamma)
+        for tau1, tau2 in ((0.0, None), (0.5, -0.25), (-1.0, 1.0), (3.0, 3.0), (float("-inf"), float("-inf"))):
+            run = GpuRun(wl, params=dr.MaskParams(gamma=gamma, head_fuse=head_fuse, tau_far=tau2))
+            scores = run.block_scores()
+            rowptr, colidx, nnz, cap = run.build_mask(scores, "zscore", tau1)
+            want = o.build_mask(scores.cpu().numpy(), cls, "zscore", tau1, gap_side=gs, tau_far=tau2)
+            assert_masks_equal(rowptr, colidx, nnz, want)
+            if tau1 == float("-inf"):             # everything passes: the candidate set itself
+                assert int(nnz[0, 0]) == int((cls != 0).sum())
+
+
+def test_zscore_constant_scores_and_fallback():
+    """sigma = 0: z = 0 everywhere, so tau <= 0 keeps every candidate and tau > 0 keeps one block per candidate set."""
+    wl = tiny_case("tiny8")
+    run = GpuRun(wl, params=dr.MaskParams(gamma=3.0))
+    cls = oracle_class_map(wl, gamma=3.0)
+    gs = o.block_frame_gap(wl.N, wl.Nt, wl.Bs)
+    scores = torch.full((wl.B, 1, wl.Sb, wl.Sb), 0.375, dtype=torch.float32, device="cuda")
+    for tau in (0.0, 0.5):
+        rowptr, colidx, nnz, cap = run.build_mask(scores, "zscore", tau)
+        assert_masks_equal(rowptr, colidx, nnz, o.build_mask(scores.cpu().numpy(), cls, "zscore", tau, gap_side=gs))
+    n_sets = sum(len({(int(g), int(s)) for g, s, c in zip(gs[0][qb], gs[1][qb], cls[qb]) if c in (1, 2)})
+                 for qb in range(wl.Sb))
+    assert int(nnz[0, 0]) == int((cls == 3).sum()) + n_sets
+
+
+@pytest.mark.parametrize("wl", CASES, ids=_ids)
+def test_uniform_masks_bit_exact_and_score_free(wl):
+    cls = oracle_class_map(wl, gamma=3.0)
+    shape_only = np.zeros((wl.B, 1, wl.Sb, wl.Sb), dtype=np.float32)
+    for ratio, ratio_far, seed in ((0.3, -1.0, 0), (0.3, 0.1, 1), (1.0, -1.0, 20470), (0.001, 0.5, 0xFFFFFFFF)):
+        run = GpuRun(wl, params=dr.MaskParams(gamma=3.0, ratio_far=ratio_far, seed=seed))
+        rowptr, colidx, nnz, cap = run.build_mask(None, "uniform", ratio)          # no scores at all
+        want = o.build_mask(shape_only, cls, "uniform", ratio, ratio_far=ratio_far, seed=seed)
+        assert_masks_equal(rowptr, colidx, nnz, want)
+        scores = run.block_scores()
+        rowptr2, colidx2, nnz2, _ = run.build_mask(scores, "uniform", ratio)
+        assert torch.equal(rowptr, rowptr2) and torch.equal(nnz, nnz2)
+        assert torch.equal(colidx[0, 0, :int(nnz[0, 0])], colidx2[0, 0, :int(nnz[0, 0])])
+
+
+def test_paper_modes_feed_the_attention_stage():
+    """scores -> z-score mask -> attention and uniform mask -> attention, checked like the other pipelines."""
+    from test_gpu_parity import ATTN_TOL, _attention_check
+    wl = tiny_case("ragged128")
+    run = GpuRun(wl, params=dr.MaskParams(gamma=3.0, tau_far=0.2, seed=3))
+    scores = run.block_scores()
+    every = [(b, h, None) for b in range(wl.B) for h in range(wl.H)]
+    for mode, par in (("zscore", 0.4), ("uniform", 0.3)):
+        rowptr, colidx, nnz, cap = run.build_mask(scores, mode, par)
+        _attention_check(run, rowptr, colidx, cap, every, ATTN_TOL[wl.dtype])
+
+
+def test_paper_mode_arguments_are_checked():
+    wl = tiny_case("tiny8")
+    run = GpuRun(wl)
+    scores = run.block_scores()
+    with pytest.raises(dr.DRError):
+        run.build_mask(scores, "zscore", float("nan"))
+    with pytest.raises(dr.DRError):
+        run.build_mask(None, "zscore", 0.5)              # scores are required outside the uniform mode
+    with pytest.raises(dr.DRError):
+        run.build_mask(scores, "uniform", 1.5)
+    bad = dr.MaskParams()
+    bad.has_tau_far = 2
+    run.params = bad
+    with pytest.raises(dr.DRError):
+        run.build_mask(scores, "zscore", 0.5)

@@ -84,3 +84,21 @@ def test_per_head_masks_full(name):
     for mode, par in (("static", 0.2), ("dynamic", 0.9)):
         rowptr, colidx, nnz, cap = run.build_mask(scores, mode, par)
         assert_masks_equal(rowptr, colidx, nnz, oracle_masks_from(scores, cls, mode, par))
+
+
+@pytest.mark.parametrize("name,heads", [("cfg3", [0, 1]), ("cfg4", [0, 1]), ("cfg5", [0, 1])])
+def test_paper_selection_rules_full(name, heads):
+    """The paper's own rules (z-score thresholds of Eqs. 10-11, seeded uniform sample of Eq. 8) at the full geometries:
+    masks bit-exact against the oracle selecting from the GPU's fp32 scores."""
+    wl = CONFIGS[name]
+    cls = oracle_class_map(wl)
+    gs = o.block_frame_gap(wl.N, wl.Nt, wl.Bs)
+    run = GpuRun(wl, heads=heads, params=dr.MaskParams(tau_far=0.8, ratio_far=0.02, seed=wl.index))
+    scores = run.block_scores()
+    s_host = scores.cpu().numpy()
+    rowptr, colidx, nnz, cap = run.build_mask(scores, "zscore", 0.3)
+    assert_masks_equal(rowptr, colidx, nnz, o.build_mask(s_host, cls, "zscore", 0.3, gap_side=gs, tau_far=0.8))
+    print(f"[{name}] zscore nnz={int(nnz[0, 0])} sparsity={1 - int(nnz[0, 0]) / wl.Sb ** 2:.4f}", flush=True)
+    rowptr, colidx, nnz, cap = run.build_mask(None, "uniform", 0.05)
+    assert_masks_equal(rowptr, colidx, nnz, o.build_mask(s_host, cls, "uniform", 0.05, ratio_far=0.02, seed=wl.index))
+    print(f"[{name}] uniform nnz={int(nnz[0, 0])} sparsity={1 - int(nnz[0, 0]) / wl.Sb ** 2:.4f}", flush=True)
