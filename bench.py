@@ -124,6 +124,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg4")
     ap.add_argument("--heads", type=int, default=0, help="use only the first H heads (0 = the workload's own count)")
+    ap.add_argument("--block-size", type=int, default=0, help="override the workload's block size Bs (32, 64 or 128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three plain 1 GiB device copies (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -148,6 +149,9 @@ def main():
         print(json.dumps({"calibration": "3 x copy of 1 GiB (reads 1048576 KiB, writes 1048576 KiB per copy)"}))
         return
     wl = CONFIGS[args.config]
+    if args.block_size:
+        import dataclasses
+        wl = dataclasses.replace(wl, Bs=args.block_size)
     H = args.heads or wl.H
     dev = "cuda:0"
     t0 = time.time()
@@ -234,9 +238,9 @@ def main():
         "dense_equivalent_tflops": round(dense_flop / (ms_attn * 1e-3) / 1e12, 1),
         "pct_bf16_mfma_peak": round(100.0 * eff_tflops / PEAK_BF16_TFLOPS, 2),
         "paper_context": "paper reports 1.7x-2.5x end-to-end speedup at >80% sparsity on NVIDIA H100 (not comparable)",
-        "roofline": {"kernel": "k_attn_mfma", "bound": "mfma", "achieved": round(eff_tflops, 1),
+        "roofline": {"kernel": {128: "k_attn_mfma", 64: "k_attn_mfma_bs64", 32: "k_attn_mfma_bs32"}.get(wl.Bs, "k_attn_generic"), "bound": "mfma", "achieved": round(eff_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(eff_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": read_traffic(f"k_attn_mfma_{args.config}"),
+                     "traffic": read_traffic(f"k_attn_mfma_{args.config}") if wl.Bs == 128 else None,
                      "flop_per_launch": flop, "avg_launch_ms": round(ms_attn, 4)},
     }
     # Shader clock while the attention kernel runs (separate, untimed pass): a one-wave probe on a side stream

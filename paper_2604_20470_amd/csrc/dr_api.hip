@@ -349,6 +349,7 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
     a.bf16 = shape->dtype == DR_BF16;
     hipStream_t s = (hipStream_t)stream;
     if (attn_mfma_supported(a)) DR_HIP(ctx, launch_attn_mfma(a, s));
+    else if (attn_mfma_small_supported(a)) DR_HIP(ctx, launch_attn_mfma_small(a, s));
     else DR_HIP(ctx, launch_attn_generic(a, s));
     return DR_OK;
 }

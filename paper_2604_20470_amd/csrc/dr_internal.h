@@ -76,6 +76,9 @@ hipError_t launch_attn_generic(const AttnArgs& a, hipStream_t s);
 // bf16 storage, d = 128, Bs = 128: MFMA path.  Returns hipErrorNotSupported for other shapes.
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_supported(const AttnArgs& a);
+// bf16 storage, d = 128, Bs = 32 or 64: MFMA path that walks the union of the CSR rows of a 128-query group.
+hipError_t launch_attn_mfma_small(const AttnArgs& a, hipStream_t s);
+bool attn_mfma_small_supported(const AttnArgs& a);
 
 // ---- measurement aid ---------------------------------------------------------------------
 // out[0] = shader-clock ticks, out[1] = 100 MHz ticks elapsed over a window of window_ticks (100 MHz units).

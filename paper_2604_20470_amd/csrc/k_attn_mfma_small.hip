@@ -1,0 +1,479 @@
+// Stage (c), MFMA path for the small block sizes: block-sparse flash-attention forward for bf16, d = 128,
+// Bs = 32 or 64 (paper Eqs. 12-13 with epsilon -> 0; block sizes of its hyper-parameter table).  gfx950 only.
+//
+// The tiling is the one of the Bs = 128 kernel (4 wavefronts x 32 query rows, 64-key chunks staged through LDS
+// with direct-to-LDS loads, S^T = K Q^T and O^T += V^T P^T on v_mfma_f32_32x32x16_bf16, softmax statistics in
+// registers), but a workgroup's 128 query rows now span 128 / Bs query blocks, each with its own row of the CSR.
+// The workgroup walks the ascending UNION of those rows: a key block is fetched into LDS once and every wavefront
+// whose query block lists it multiplies against it; the others only take part in the loads and the barrier.
+// Neighbouring query blocks share most of their key blocks (the never-pruned zone of a frame), so the gather
+// traffic per useful flop stays close to that of Bs = 128 instead of growing 4x or 16x.
+//   Bs = 64: a chunk is one key block; wavefronts 0-1 and 2-3 follow their own row.
+//   Bs = 32: a chunk is two consecutive entries of the union (keys 0..31 and 32..63 of the tile come from different
+//            places); every wavefront follows its own row and may use either half, both or none (a half it does
+//            not own is masked like keys past the end of the sequence).
+#include "dr_internal.h"
+
+#include <type_traits>
+
+namespace dr {
+namespace {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kD = 128;
+constexpr int kRowsPerGroup = 128;                   // query rows per workgroup
+constexpr int kWaves = 4, kThreads = kWaves * 64;
+constexpr int kChunkKeys = 64;
+constexpr int kRowBytes = kD * 2;
+constexpr int kTileBytes = kChunkKeys * kRowBytes;   // 16 KB per operand per stage
+constexpr int kStageBytes = 2 * kTileBytes;          // K then V
+constexpr int kLdsBytes = 2 * kStageBytes;
+constexpr float kSumLimit = 1024.0f;                 // a lane's probabilities of a chunk may sum to at most this
+constexpr int kNoBlock = 0x7fffffff;
+
+#define DR_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+#define DR_WAIT_VMCNT0() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
+
+// direct-to-LDS 16-byte load, hand-tracked (see the Bs = 128 kernel for why it goes through inline assembly)
+__device__ __forceinline__ void dma16(uint32_t voff, uint64_t base, uint32_t m0_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(base), "s"(m0_base) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+__device__ __forceinline__ uint64_t uniform64(uint64_t x) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ float max_across_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+struct LoadPlan {
+    uint32_t koff, voff;     // per-lane byte offset inside a 16-row group, swizzle folded in
+    uint32_t m0_k;           // LDS address of this wave's first K piece in stage 0
+    int64_t row_bytes;
+    int r_first;             // tile row of this lane in the wave's first piece (0..15)
+    int piece;
+};
+
+// One chunk of the union walk: up to two key blocks and, per key block, the set of CSR rows (bit l = row l of the
+// workgroup) that list it.
+struct Chunk {
+    int kb0, kb1;            // kb1 < 0: no second block (Bs = 64 always; Bs = 32 at the odd end of the union)
+    uint32_t rows0, rows1;
+    bool valid;
+};
+
+// Tile rows 32 * part .. 32 * part + 31 <- the 32 tokens key0 .. key0 + 31; tokens past last_row re-read last_row
+// (finite values; the logits of such keys are masked).  Wave w moves pieces w, w+4, w+8, w+12 of 4 rows: its pieces
+// 2 * part and 2 * part + 1 fall into this part.
+template <int STAGE>
+__device__ __forceinline__ void issue_part(const LoadPlan& lp, const char* Kh, const char* Vh, int key0, int part,
+                                           int last_row) {
+    const uint32_t m0 = lp.m0_k + STAGE * kStageBytes + part * 8192;
+    if (key0 + 31 <= last_row) {
+        const uint64_t kbase = uniform64((uint64_t)(Kh + (int64_t)key0 * lp.row_bytes));
+        const uint64_t vbase = uniform64((uint64_t)(Vh + (int64_t)key0 * lp.row_bytes));
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint64_t step = (uint64_t)(16 * i) * (uint64_t)lp.row_bytes;
+            dma16(lp.koff, kbase + step, m0 + i * 4096);
+            dma16(lp.voff, vbase + step, m0 + kTileBytes + i * 4096);
+        }
+    } else {
+        const int base_row = min(key0, last_row);
+        const uint64_t kbase = uniform64((uint64_t)(Kh + (int64_t)base_row * lp.row_bytes));
+        const uint64_t vbase = uniform64((uint64_t)(Vh + (int64_t)base_row * lp.row_bytes));
+        int r_first = lp.r_first;
+        asm volatile("" : "+v"(r_first));  // keeps the clamped offsets of this rare path from being hoisted out of the loop
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = r_first + 16 * i;                          // row inside the part
+            const int rc = min(key0 + r, last_row) - base_row;       // >= 0
+            const uint32_t ko = (uint32_t)(rc * lp.row_bytes) + ((lp.piece ^ (r & 15)) << 4);
+            const uint32_t vo = (uint32_t)(rc * lp.row_bytes) + ((lp.piece ^ ((r & 3) << 2)) << 4);
+            dma16(ko, kbase, m0 + i * 4096);
+            dma16(vo, vbase, m0 + kTileBytes + i * 4096);
+        }
+    }
+}
+
+struct State {
+    v16f o[4];
+    float m_ref;
+    float l_part;
+};
+
+struct ReadPlan {
+    uint32_t k_addr[8];
+    uint32_t v_addr[4];
+};
+
+// One chunk for one wavefront.  MBM = 3: both 32-key halves of the tile are this wavefront's; MBM = 1: one half, the
+// one at byte offset sel_off of the K and V tiles (0 or 32 rows).  valid0 / valid1: number of real keys in the
+// (first / second) half processed (>= 32: all).
+template <int STAGE, int MBM, class F>
+__device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[8], State& st, bool& first,
+                                           int valid0, int valid1, uint32_t sel_off, int half, F&& issue) {
+    typedef __attribute__((address_space(3))) const v8bf* lds_v8;
+    typedef __attribute__((address_space(3))) v4s* lds_v4;
+    constexpr uint32_t kK = STAGE * kStageBytes, kV = STAGE * kStageBytes + kTileBytes;
+    constexpr int MB0 = (MBM & 1) ? 0 : 1, MB1 = (MBM & 2) ? 2 : 1;     // active key sub-blocks: MB0 .. MB1 - 1
+
+    // Register budget: the logit fragments are read in two batches of four contraction steps and the V^T fragments
+    // one key sub-block at a time (the second one into the registers the logits vacate), so that the variants
+    // of this body and the union walk fit the 256 registers of a wave without spilling into the loop.
+    auto read_v = [&](int mb, v8bf (&dst)[2][4]) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                union { struct { v4s a, b; } s2; v8bf v; } u;
+                u.s2.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + kV + sel_off + (mb * 32 + t * 16) * kRowBytes));
+                u.s2.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + kV + sel_off + (mb * 32 + t * 16 + 8) * kRowBytes));
+                dst[t][db] = u.v;
+            }
+    };
+    v16f s[2];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { s[0][j] = 0.f; s[1][j] = 0.f; }
+#pragma unroll
+    for (int batch = 0; batch < 2; ++batch) {
+        v8bf kf[2][4];
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+            for (int mb = MB0; mb < MB1; ++mb)
+                kf[mb][k4] = *(lds_v8)(uintptr_t)(rd.k_addr[batch * 4 + k4] + kK + sel_off + mb * 32 * kRowBytes);
+        __builtin_amdgcn_sched_barrier(0);
+        if (batch == 0) {
+            issue();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+            for (int mb = MB0; mb < MB1; ++mb)
+                s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][k4], qf[batch * 4 + k4], s[mb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    v8bf vfa[2][4];
+    read_v(MB0, vfa);                              // lands while the softmax runs
+    __builtin_amdgcn_sched_barrier(0);
+
+    // logits relative to the exponent reference (this kernel keeps no -m_ref accumulator operand: 16 registers less)
+#pragma unroll
+    for (int mb = MB0; mb < MB1; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[mb][j] -= st.m_ref;
+    // keys past the end of the sequence (only in the last key block)
+    if (valid0 < 32 || valid1 < 32) {
+        int h4 = half * 4;
+        asm volatile("" : "+v"(h4));       // keeps the sixteen per-lane key indices from being hoisted out of the loop
+#pragma unroll
+        for (int mb = MB0; mb < MB1; ++mb) {
+            const int valid = mb ? valid1 : valid0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if ((j >> 2) * 8 + h4 + (j & 3) >= valid) s[mb][j] = -INFINITY;
+        }
+    }
+
+    v8bf pf[2][2];
+    v2bf ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
+    auto exps = [&](float& lsum) {
+#pragma unroll
+        for (int mb = MB0; mb < MB1; ++mb)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) {
+                    v2bf pk;
+                    pk[0] = (__bf16)__builtin_amdgcn_exp2f(s[mb][t * 8 + i]);
+                    pk[1] = (__bf16)__builtin_amdgcn_exp2f(s[mb][t * 8 + i + 1]);
+                    lsum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lsum, false);
+                    pf[mb][t][i] = pk[0];
+                    pf[mb][t][i + 1] = pk[1];
+                }
+            }
+    };
+    float lc = 0.f;
+    if (!first) exps(lc);
+    if (first || __any(!(lc <= kSumLimit))) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int mb = MB0; mb < MB1; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[mb][j]);
+        mx = max_across_halves(mx);        // finite: the first active sub-block of a chunk starts a key block
+        const float delta = first ? mx : fmaxf(mx, 0.f);
+        const float alpha = __builtin_amdgcn_exp2f(-delta);
+        st.m_ref += delta;
+        st.l_part *= alpha;
+#pragma unroll
+        for (int mb = MB0; mb < MB1; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s[mb][j] -= delta;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) st.o[db][j] *= alpha;
+        first = false;
+        lc = 0.f;
+        exps(lc);
+    }
+    st.l_part += lc;
+
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+            st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa[t][db], pf[MB0][t], st.o[db], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (MBM == 3) {
+        read_v(1, vfa);                            // same registers: their first contents were consumed at issue
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+                st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa[t][db], pf[1][t], st.o[db], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// grid: (ceil(N / 128) * H * B) in one dimension, dealt to the XCDs as contiguous runs (see the Bs = 128 kernel).
+template <int BS>
+__device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
+    constexpr int L = kRowsPerGroup / BS;          // CSR rows per workgroup: 2 or 4
+    constexpr int kWavesPerRow = kWaves / L;       // 2 or 1
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    constexpr int kXcds = 8;
+    const int N = a.td.N;
+    const int groups = (N + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int total_items = groups * a.td.H * a.td.B;
+    const int per_xcd = (total_items + kXcds - 1) / kXcds;
+    const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (item >= total_items) return;
+    const int qg = item % groups, h = (item / groups) % a.td.H, b = item / (groups * a.td.H);
+    const int64_t row_bytes = a.td.stride_n * 2;
+    const int64_t head_off = ((int64_t)b * a.td.stride_b + (int64_t)h * a.td.stride_h) * 2;
+    const char* Qh = reinterpret_cast<const char*>(a.Q) + head_off;
+    const char* Kh = reinterpret_cast<const char*>(a.K) + head_off;
+    const char* Vh = reinterpret_cast<const char*>(a.V) + head_off;
+    const int mh = (a.mask_heads == 1) ? 0 : h;
+    const int32_t* rp = a.rowptr + ((int64_t)b * a.mask_heads + mh) * (a.Sb + 1);
+    const int32_t* ci = a.colidx + ((int64_t)b * a.mask_heads + mh) * a.colidx_stride;
+
+    const float cs = 1.4426950408889634f / sqrtf((float)kD);
+    const int q_wave0 = qg * kRowsPerGroup + wave * 32;
+    v8bf qf[8];
+    {
+        const int qrow = min(q_wave0 + l32, N - 1);
+        const char* src = Qh + (int64_t)qrow * row_bytes + half * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const v8bf raw = *reinterpret_cast<const v8bf*>(src + ks * 32);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qf[ks][i] = (__bf16)((float)raw[i] * cs);
+        }
+    }
+
+    const uint32_t lds0 = lds_addr(smem);
+    LoadPlan lp;
+    lp.row_bytes = row_bytes;
+    lp.piece = lane & 15;
+    lp.r_first = wave * 4 + (lane >> 4);
+    lp.koff = (uint32_t)(lp.r_first * row_bytes) + ((lp.piece ^ (lp.r_first & 15)) << 4);
+    lp.voff = (uint32_t)(lp.r_first * row_bytes) + ((lp.piece ^ ((lp.r_first & 3) << 2)) << 4);
+    lp.m0_k = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
+
+    ReadPlan rd;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) rd.k_addr[ks] = lds0 + l32 * kRowBytes + (((ks * 2 + half) ^ (l32 & 15)) << 4);
+    {
+        const int v_e = (lane & 15) >> 2, v_c = lane & 3, v_grp = (lane >> 4) & 1;
+        const int r0 = half * 4 + v_e;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const int piece = db * 4 + v_grp * 2 + (v_c >> 1);
+            rd.v_addr[db] = lds0 + r0 * kRowBytes + ((piece ^ (v_e << 2)) << 4) + (v_c & 1) * 8;
+        }
+    }
+
+    State st;
+    st.m_ref = 0.f;
+    st.l_part = 0.f;
+    bool first = true;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) st.o[db][j] = 0.f;
+
+    // ---- the L rows of the CSR this workgroup follows, each through a 64-entry register window ----
+    int beg[L], cnt[L], pos[L], win[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        const int qb = qg * L + l;
+        beg[l] = (qb < a.Sb) ? __builtin_amdgcn_readfirstlane(rp[qb]) : 0;
+        cnt[l] = (qb < a.Sb) ? __builtin_amdgcn_readfirstlane(rp[qb + 1]) - beg[l] : 0;
+        pos[l] = 0;
+        win[l] = (cnt[l] > 0) ? ci[beg[l] + min(lane, cnt[l] - 1)] : 0;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
+#pragma unroll
+    for (int l = 0; l < L; ++l) asm volatile("" : "+v"(win[l]));
+    // next entry of the ascending union: its key block and the rows that list it (clamped: memory safety)
+    auto next_entry = [&](int& kb, uint32_t& rows) {
+        int head[L];
+        kb = kNoBlock;
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            head[l] = (pos[l] < cnt[l]) ? min(max(__builtin_amdgcn_readlane(win[l], pos[l] & 63), 0), a.Sb - 1) : kNoBlock;
+            kb = min(kb, head[l]);
+        }
+        rows = 0;
+        if (kb == kNoBlock) return;
+#pragma unroll
+        for (int l = 0; l < L; ++l)
+            if (head[l] == kb) {
+                rows |= 1u << l;
+                ++pos[l];
+                if ((pos[l] & 63) == 0 && pos[l] < cnt[l]) {
+                    win[l] = ci[beg[l] + min(pos[l] + lane, cnt[l] - 1)];
+                    asm volatile("" : "+v"(win[l]));
+                }
+            }
+    };
+    auto fetch = [&]() {
+        Chunk c;
+        next_entry(c.kb0, c.rows0);
+        c.valid = c.kb0 != kNoBlock;
+        c.kb1 = -1;
+        c.rows1 = 0;
+        if (BS == 32 && c.valid) {
+            next_entry(c.kb1, c.rows1);
+            if (c.kb1 == kNoBlock) { c.kb1 = -1; c.rows1 = 0; }
+        }
+        if (BS == 64) c.rows1 = c.rows0;
+        return c;
+    };
+    auto issue0 = [&](const Chunk& c) {
+        if (BS == 64) { issue_part<0>(lp, Kh, Vh, c.kb0 * 64, 0, N - 1); issue_part<0>(lp, Kh, Vh, c.kb0 * 64 + 32, 1, N - 1); }
+        else { issue_part<0>(lp, Kh, Vh, c.kb0 * 32, 0, N - 1); issue_part<0>(lp, Kh, Vh, (c.kb1 >= 0 ? c.kb1 : c.kb0) * 32, 1, N - 1); }
+    };
+    auto issue1 = [&](const Chunk& c) {
+        if (BS == 64) { issue_part<1>(lp, Kh, Vh, c.kb0 * 64, 0, N - 1); issue_part<1>(lp, Kh, Vh, c.kb0 * 64 + 32, 1, N - 1); }
+        else { issue_part<1>(lp, Kh, Vh, c.kb0 * 32, 0, N - 1); issue_part<1>(lp, Kh, Vh, (c.kb1 >= 0 ? c.kb1 : c.kb0) * 32, 1, N - 1); }
+    };
+    const int my_row = wave / kWavesPerRow;
+    // A wavefront that owns only one half of a Bs = 32 chunk still runs the full body with the other half's valid
+    // count set to 0 (logits -inf, probabilities 0, finite V): one body variant keeps the kernel inside its register
+    // budget; the price is the idle half's matrix instructions.
+    auto run_chunk = [&](auto stage_tag, const Chunk& c, auto&& issue) {
+        constexpr int STAGE = decltype(stage_tag)::value;
+        const int mbm = (int)((c.rows0 >> my_row) & 1u) | (int)(((c.rows1 >> my_row) & 1u) << 1);
+        const int valid0 = N - c.kb0 * BS;
+        if (BS == 64) {
+            if (mbm == 3) chunk_body<STAGE, 3>(rd, qf, st, first, valid0, valid0 - 32, 0u, half, issue);
+            else issue();
+        } else {
+            const int valid1 = (c.kb1 >= 0) ? N - c.kb1 * BS : 0;
+            if (mbm != 0) chunk_body<STAGE, 3>(rd, qf, st, first, (mbm & 1) ? valid0 : 0, (mbm & 2) ? valid1 : 0, 0u, half, issue);
+            else issue();
+        }
+    };
+
+    Chunk cur = fetch();
+    if (cur.valid) {
+        issue0(cur);
+        DR_WAIT_VMCNT0();
+        // invariant at each barrier: every wave has waited for its share of the chunk about to be consumed and has
+        // finished reading the previous one, whose stage the next loads overwrite
+        while (true) {
+            Chunk nxt = fetch();
+            DR_BARRIER();
+            run_chunk(std::integral_constant<int, 0>{}, cur, [&]() { if (nxt.valid) issue1(nxt); });
+            DR_WAIT_VMCNT0();
+            if (!nxt.valid) break;
+            cur = nxt;
+            nxt = fetch();
+            DR_BARRIER();
+            run_chunk(std::integral_constant<int, 1>{}, cur, [&]() { if (nxt.valid) issue0(nxt); });
+            DR_WAIT_VMCNT0();
+            if (!nxt.valid) break;
+            cur = nxt;
+        }
+    }
+
+    // ---- epilogue ----
+    char* Oh = reinterpret_cast<char*>(a.O) + head_off;
+    const float l = st.l_part + __shfl_xor(st.l_part, 32);
+    const float inv = (l > 0.f) ? 1.0f / l : 0.f;
+    const int qrow = q_wave0 + l32;
+    if (qrow < N) {
+        char* dst = Oh + (int64_t)qrow * row_bytes;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                v4bf v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (__bf16)(st.o[db][g * 4 + i] * inv);
+                *reinterpret_cast<v4bf*>(dst + (db * 32 + g * 8 + half * 4) * 2) = v;
+            }
+        if (a.lse && half == 0)
+            a.lse[((int64_t)b * a.td.H + h) * N + qrow] =
+                (l > 0.f) ? st.m_ref * 0.6931471805599453f + logf(l) : -INFINITY;
+    }
+}
+
+// Bs = 64 fits two workgroups per CU (256 registers per wave).  The Bs = 32 walk keeps four CSR rows in flight and
+// does not fit that budget without spilling into the loop (and a spill reload would wait on the tile loads in
+// flight), so it runs one workgroup per CU with the larger register file.
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma_bs64(AttnArgs a) {
+    attn_small_body<64>(a);
+}
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_bs32(AttnArgs a) {
+    attn_small_body<32>(a);
+}
+
+template <class Kern>
+hipError_t launch_small(Kern kern, const AttnArgs& a, hipStream_t s) {
+    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (attr != hipSuccess) return attr;
+    const int groups = (a.td.N + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int total = groups * a.td.H * a.td.B;
+    const int grid = (total + 7) / 8 * 8;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_mfma_small_supported(const AttnArgs& a) {
+    return a.bf16 && a.td.d == kD && (a.Bs == 32 || a.Bs == 64) && a.td.stride_n * 2 * kChunkKeys < (1ll << 31);
+}
+
+hipError_t launch_attn_mfma_small(const AttnArgs& a, hipStream_t s) {
+    if (!attn_mfma_small_supported(a)) return hipErrorNotSupported;
+    return a.Bs == 32 ? launch_small(k_attn_mfma_bs32, a, s) : launch_small(k_attn_mfma_bs64, a, s);
+}
+
+}  // namespace dr

@@ -102,3 +102,24 @@ def test_paper_selection_rules_full(name, heads):
     rowptr, colidx, nnz, cap = run.build_mask(None, "uniform", 0.05)
     assert_masks_equal(rowptr, colidx, nnz, o.build_mask(s_host, cls, "uniform", 0.05, ratio_far=0.02, seed=wl.index))
     print(f"[{name}] uniform nnz={int(nnz[0, 0])} sparsity={1 - int(nnz[0, 0]) / wl.Sb ** 2:.4f}", flush=True)
+
+
+@pytest.mark.parametrize("name,bs", [("cfg3", 64), ("cfg3", 32), ("cfg4", 64)])
+def test_small_block_sizes_full(name, bs):
+    """The benchmark geometries at Bs = 64 / 32 (MFMA path that walks the union of several CSR rows): scores, masks in
+    full, attention on sampled query blocks."""
+    import dataclasses
+    wl = dataclasses.replace(CONFIGS[name], Bs=bs)
+    rng = np.random.default_rng(2000 + wl.index + bs)
+    run = GpuRun(wl, heads=[0, 1, 9])
+    cls = oracle_class_map(wl)
+    assert (run.class_map().cpu().numpy() == cls).all()
+    scores = run.block_scores()
+    want = o.block_scores(to_f64(run.Qc[:, :2]), to_f64(run.Kc[:, :2]), wl.Bs, 2)
+    assert score_error(scores, want) <= SCORE_TOL
+    rowptr, colidx, nnz, cap = run.build_mask(scores, "static", 0.08)
+    assert_masks_equal(rowptr, colidx, nnz, oracle_masks_from(scores, cls, "static", 0.08))
+    print(f"[{name} Bs={bs}] Sb={wl.Sb} nnz={int(nnz[0, 0])} sparsity={1 - int(nnz[0, 0]) / wl.Sb ** 2:.4f}", flush=True)
+    sample = [(0, hi, _sample_rows(wl, rng, 4)) for hi in (0, 2)]
+    worst = _attention_check(run, rowptr, colidx, cap, sample, ATTN_TOL[wl.dtype])
+    print(f"[{name} Bs={bs}] attention max-abs err {worst:.3e} on {sample}", flush=True)
