@@ -80,6 +80,9 @@ CONFIGS: Dict[str, Workload] = {
     "cfg4": Workload("cfg4", 4, 1, 40, 128, 21, 45, 80, 128, "bf16", "field", "static", None, None, 0.5,
                      target_sparsity=0.85),
     "cfg5": Workload("cfg5", 5, 1, 24, 128, 33, 45, 80, 128, "bf16", "blob", "dynamic", None, 0.95, 0.7),
+    # the shape of the paper's layer micro-benchmark (selector overhead appendix): ~264K tokens, block size 32
+    "micro264k": Workload("micro264k", 6, 1, 24, 128, 33, 80, 100, 32, "bf16", "field", "static", None, None, 0.5,
+                          target_sparsity=0.85),
 }
 
 
