@@ -30,6 +30,10 @@ Stages, in the order of the method (paper sections in brackets):
   build_mask        all rows -> CSR (rowptr, colidx)  [Algorithm 1's output M_b]
   masked_attention  softmax over exactly the keys of the kept blocks
                     [Eqs. 12-13 with epsilon -> 0]
+  attention_matrix / proxy_loss   the row-normalised attention matrix under a
+                    block mask and the offline-search objective built on it:
+                    normalised squared error against the dense matrix plus the
+                    sparsity penalty  [App. C: proxy attention, Eq. 22]
 
 Readings taken where the text leaves a choice (each is a deliberate
 interpretation, listed again in the design notes):
@@ -557,3 +561,37 @@ def csr_to_token_mask(rowptr: np.ndarray, colidx: np.ndarray, Bs: int, N: int) -
             c0, c1 = _block_range(int(kb), Bs, N)
             M[r0:r1, c0:c1] = True
     return M
+
+
+# --------------------------------------------------------------------------- #
+# evaluation utility: the proxy-task objective of the offline search
+# --------------------------------------------------------------------------- #
+def attention_matrix(Q: np.ndarray, K: np.ndarray, rowptr: Optional[np.ndarray] = None,
+                     colidx: Optional[np.ndarray] = None, Bs: int = 0) -> np.ndarray:
+    """Row-normalised attention matrix A[p, q] proportional to exp(Q_p . K_q / sqrt(d)) over the keys the block CSR
+    keeps for p's query block (all keys if no CSR is given); rows with no key are zero.  Q, K: [N, d]."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    N, d = Q.shape
+    S = (Q @ K.T) / math.sqrt(d)
+    if rowptr is not None:
+        M = csr_to_token_mask(np.asarray(rowptr), np.asarray(colidx), Bs, N)
+        S = np.where(M, S, -np.inf)
+    A = np.zeros((N, N))
+    for p in range(N):
+        row = S[p]
+        m = row.max()
+        if np.isfinite(m):
+            e = np.exp(row - m)
+            A[p] = e / e.sum()
+    return A
+
+
+def proxy_loss(A_dense: np.ndarray, A_sparse: np.ndarray, sparsity: float, target: float = 0.80,
+               alpha: float = 10.0) -> Tuple[float, float]:
+    """Objective of the offline search: ||A_dense - A_sparse||_F^2 / ||A_dense||_F^2 + alpha * max(0, target - sparsity).
+    Returns (loss, normalised squared error)."""
+    num = float(((A_dense - A_sparse) ** 2).sum())
+    den = float((A_dense ** 2).sum())
+    nmse = num / den
+    return nmse + alpha * max(0.0, target - sparsity), nmse

@@ -6,4 +6,5 @@ window geometry, no selection, no attention.  Both the CPU oracle's tests and
 the GPU path's tests/bench draw their inputs from here so that they see the
 same bits.
 """
-from .generate import CONFIGS, Workload, get_workload, make_head, make_qkv, tiny_case  # noqa: F401
+from .generate import (CONFIGS, Workload, get_workload, make_ar1_proxy, make_head, make_qkv,  # noqa: F401
+                       tiny_case)

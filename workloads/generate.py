@@ -176,3 +176,16 @@ def make_qkv(wl: Workload, heads=None, device: str = "cpu"):
             for dst, src in zip(out, make_head(wl, b, h)):
                 dst[b, i].copy_(round_to_dtype(src, wl.dtype))
     return out
+
+
+def make_ar1_proxy(Nf: int, Nt: int, D: int, delta: float, seed: int) -> np.ndarray:
+    """Hidden states of the drift proxy: h[t] = sqrt(1 - delta^2) h[t-1] + delta eps[t], eps ~ N(0, I), per token
+    position, h[0] ~ N(0, I).  Returns float32 [Nf * Nt, D], frame-major like the video token order.
+    (Input synthesis only: the three motion regimes of the proxy task use delta = 0.02, 0.15, 0.40.)"""
+    g = np.random.Generator(np.random.Philox(np.random.SeedSequence([BASE_SEED, 7, seed])))
+    h = np.empty((Nf, Nt, D), dtype=np.float64)
+    h[0] = g.standard_normal((Nt, D))
+    keep = math.sqrt(1.0 - delta * delta)
+    for t in range(1, Nf):
+        h[t] = keep * h[t - 1] + delta * g.standard_normal((Nt, D))
+    return h.reshape(Nf * Nt, D).astype(np.float32)
