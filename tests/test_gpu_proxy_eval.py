@@ -1,0 +1,39 @@
+"""The proxy-task objective (App. C, Eq. 22) evaluated through the GPU stages against the oracle's value."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_20470_amd as dr
+from paper_2604_20470_amd import proxy_eval
+from oracle import dynamicrad_oracle as o
+from workloads import make_ar1_proxy
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("delta", [0.02, 0.15, 0.40])
+def test_proxy_objective_matches_the_oracle(delta):
+    Nf, Hg, Wg, D, Bs = 8, 8, 8, 64, 32
+    Nt, N = Hg * Wg, Nf * Hg * Wg
+    h = make_ar1_proxy(Nf, Nt, D, delta, seed=11)                      # Q = K = h (the proxy's hidden states)
+    Q = torch.from_numpy(h).view(1, 1, N, D).cuda()
+    ctx = dr.Context(0)
+    tab = o.frame_table(Nf, Nt, Bs, 2.0, 1.0)
+    cls = o.classify_blocks(N, Nt, Bs, tab, 0.15, 0.60)
+    gs = o.block_frame_gap(N, Nt, Bs)
+    hd = h.astype(np.float64)
+    A_dense = o.attention_matrix(hd, hd)
+    for mode, code, par, kw in (("static", dr.MODE_STATIC, 0.3, {}), ("dynamic", dr.MODE_DYNAMIC, 0.8, {}),
+                                ("zscore", dr.MODE_ZSCORE, 0.5, {"gap_side": gs})):
+        params = dr.MaskParams(gamma=2.0, head_fuse=1)
+        loss, nmse, sparsity = proxy_eval.proxy_loss(ctx, Q, Q, Nf, Hg, Wg, Bs, code, par, 1.0, params)
+        # the oracle selects from the GPU's own fp32 scores (bit-exact masks), then forms the matrices in fp64
+        shape = dr.shape_of(Q, Nf, Hg, Wg, Bs)
+        scores = torch.empty((1, 1, shape.Sb, shape.Sb), dtype=torch.float32, device="cuda")
+        dr.dr_block_scores(ctx, shape, Q, Q, 1, scores)
+        rp, ci = o.build_mask(scores.cpu().numpy(), cls, mode, par, **kw)[0][0]
+        want_loss, want_nmse = o.proxy_loss(A_dense, o.attention_matrix(hd, hd, rp, ci, Bs),
+                                            o.effective_sparsity(rp, shape.Sb))
+        assert abs(sparsity - o.effective_sparsity(rp, shape.Sb)) < 1e-12
+        assert abs(nmse - want_nmse) <= 1e-5 * max(1.0, want_nmse), (mode, nmse, want_nmse)
+        assert abs(loss - want_loss) <= 1e-5 * max(1.0, want_loss)
