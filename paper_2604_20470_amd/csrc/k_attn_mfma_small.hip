@@ -123,7 +123,8 @@ struct ReadPlan {
 // (first / second) half processed (>= 32: all).
 template <int STAGE, int MBM, class F>
 __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[8], State& st, bool& first,
-                                           int valid0, int valid1, uint32_t sel_off, int half, F&& issue) {
+                                           int valid0, int valid1, float init0, float init1, uint32_t sel_off, int half,
+                                           F&& issue) {
     typedef __attribute__((address_space(3))) const v8bf* lds_v8;
     typedef __attribute__((address_space(3))) v4s* lds_v4;
     constexpr uint32_t kK = STAGE * kStageBytes, kV = STAGE * kStageBytes + kTileBytes;
@@ -143,9 +144,10 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
                 dst[t][db] = u.v;
             }
     };
+    // init0 / init1: 0, or -inf for a half this wavefront does not own (its logits stay -inf, its probabilities 0)
     v16f s[2];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) { s[0][j] = 0.f; s[1][j] = 0.f; }
+    for (int j = 0; j < 16; ++j) { s[0][j] = init0; s[1][j] = init1; }
 #pragma unroll
     for (int batch = 0; batch < 2; ++batch) {
         v8bf kf[2][4];
@@ -382,19 +384,21 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
         else { issue_part<1>(lp, Kh, Vh, c.kb0 * 32, 0, N - 1); issue_part<1>(lp, Kh, Vh, (c.kb1 >= 0 ? c.kb1 : c.kb0) * 32, 1, N - 1); }
     };
     const int my_row = wave / kWavesPerRow;
-    // A wavefront that owns only one half of a Bs = 32 chunk still runs the full body with the other half's valid
-    // count set to 0 (logits -inf, probabilities 0, finite V): one body variant keeps the kernel inside its register
-    // budget; the price is the idle half's matrix instructions.
+    // A wavefront that owns only one half of a Bs = 32 chunk still runs the full body, the other half's logit
+    // accumulators starting from -inf (probabilities 0, finite V): one body variant keeps the kernel inside its
+    // register budget; the price is the idle half's matrix instructions.
     auto run_chunk = [&](auto stage_tag, const Chunk& c, auto&& issue) {
         constexpr int STAGE = decltype(stage_tag)::value;
         const int mbm = (int)((c.rows0 >> my_row) & 1u) | (int)(((c.rows1 >> my_row) & 1u) << 1);
         const int valid0 = N - c.kb0 * BS;
         if (BS == 64) {
-            if (mbm == 3) chunk_body<STAGE, 3>(rd, qf, st, first, valid0, valid0 - 32, 0u, half, issue);
+            if (mbm == 3) chunk_body<STAGE, 3>(rd, qf, st, first, valid0, valid0 - 32, 0.f, 0.f, 0u, half, issue);
             else issue();
         } else {
-            const int valid1 = (c.kb1 >= 0) ? N - c.kb1 * BS : 0;
-            if (mbm != 0) chunk_body<STAGE, 3>(rd, qf, st, first, (mbm & 1) ? valid0 : 0, (mbm & 2) ? valid1 : 0, 0u, half, issue);
+            const int valid1 = (c.kb1 >= 0) ? N - c.kb1 * BS : 32;
+            if (mbm != 0)
+                chunk_body<STAGE, 3>(rd, qf, st, first, valid0, valid1, (mbm & 1) ? 0.f : -INFINITY,
+                                     (mbm & 2) ? 0.f : -INFINITY, 0u, half, issue);
             else issue();
         }
     };
