@@ -185,8 +185,13 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
  *   mask_heads   1 (one mask per batch element shared by all heads) or H
  *   colidx_stride  distance in entries between the colidx arrays of consecutive masks
  *   lse          optional device float32 [B, H, N]: natural-log sum-exp of each row's logits
- * bf16 inputs use bf16 MFMA with fp32 accumulation and fp32 softmax; fp32 inputs are
- * computed in fp32 throughout.
+ * bf16 inputs with d = 128 use bf16 MFMA (operands Q * log2(e)/sqrt(d) re-rounded to bf16, K,
+ * V and the probabilities rounded to bf16) with fp32 accumulation and fp32 softmax, for every
+ * block size; fp32 inputs, and bf16 inputs with d = 64, are computed in fp32 throughout.
+ * Out-of-range key-block indices are clamped to [0, Sb) (memory safety), not reported; a row
+ * whose list is not ascending is still summed correctly (softmax does not depend on the order).
+ * Argument errors (NULL or misaligned pointers, strides, mask_heads) are rejected on the host
+ * before any launch; the call itself is asynchronous on `stream`.
  */
 dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, const void* V,
                              const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads,
@@ -203,7 +208,7 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
  * pointer or a window out of range. */
 dr_status dr_clock_probe(dr_ctx* ctx, uint64_t window_us, uint64_t* out, void* stream);
 
-/* Library version string, e.g. "dynamicrad-gfx950 0.1". */
+/* Library version string, e.g. "dynamicrad-gfx950 0.2". */
 const char* dr_version(void);
 
 #ifdef __cplusplus

@@ -194,7 +194,7 @@ dr_status ensure_geometry(dr_ctx* ctx, const dr_shape* s, double lambda, const d
 
 extern "C" {
 
-const char* dr_version(void) { return "dynamicrad-gfx950 0.1"; }
+const char* dr_version(void) { return "dynamicrad-gfx950 0.2"; }
 
 dr_status dr_create(dr_ctx** out, int device) {
     if (!out) return DR_ERR_INVALID_ARG;

@@ -375,3 +375,33 @@ def test_small_block_sizes_on_the_mfma_path(bs):
     empty = np.flatnonzero(np.diff(rps[0]) == 0)
     assert (O[0, 0, empty[0] * bs:(empty[0] + 1) * bs] == 0).all()
     _attention_check(run, rowptr, colidx, cap, every, ATTN_TOL[wl.dtype])
+
+
+@pytest.mark.parametrize("bs", [32, 64, 128])
+def test_unsorted_key_block_lists_give_the_same_attention(bs):
+    """The kernels walk a row's list in the order given (the union walk of the small block sizes takes the smallest
+    head first): a permuted list changes the summation order only."""
+    wl = tiny_case("ragged128", Bs=bs)
+    run = GpuRun(wl)
+    Sb = wl.Sb
+    rng = np.random.default_rng(7 + bs)
+    keep = rng.random((Sb, Sb)) < 0.4
+    keep[:, 0] = True
+    rp = np.concatenate([[0], np.cumsum(keep.sum(axis=1))]).astype(np.int32)
+    ci_sorted = np.nonzero(keep)[1].astype(np.int32)
+    ci_perm = ci_sorted.copy()
+    for qb in range(Sb):
+        seg = ci_perm[rp[qb]:rp[qb + 1]]
+        rng.shuffle(seg)
+    rowptr = torch.from_numpy(rp).view(1, 1, -1).contiguous().cuda()
+    outs = []
+    for ci in (ci_sorted, ci_perm):
+        colidx = torch.from_numpy(ci).view(1, 1, -1).contiguous().cuda()
+        outs.append(run.attention(rowptr, colidx, len(ci)).float())
+    assert torch.isfinite(outs[1]).all()
+    # a different order moves the exponent reference (the first chunk's maximum) and with it the bf16 rounding of
+    # every probability: the two outputs agree to the accuracy of the path, not bit for bit
+    assert (outs[0] - outs[1]).abs().max().item() <= ATTN_TOL[wl.dtype]
+    every = [(0, h, None) for h in range(wl.H)]
+    colidx = torch.from_numpy(ci_perm).view(1, 1, -1).contiguous().cuda()
+    _attention_check(run, rowptr, colidx, len(ci_perm), every, ATTN_TOL[wl.dtype])
