@@ -424,3 +424,14 @@ def test_maximum_frame_count_and_one_past_it():
     Q = torch.zeros((1, 1, 257 * 4, 64), device="cuda")
     with pytest.raises(dr.DRError, match="UNSUPPORTED"):
         dr.dr_block_scores(run.ctx, dr.shape_of(Q, 257, 2, 2, 32), Q, Q, 1, scores)
+
+
+def test_mfma_probe_runs_and_checks_its_arguments():
+    ctx = dr.Context(0)
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flop = dr.dr_mfma_probe(ctx, 8, 16, True, sink)
+    torch.cuda.synchronize()
+    assert flop == 8 * 4 * 16 * 8 * 32768.0
+    for wg, it in ((0, 16), (8, 0), (8, 12)):
+        with pytest.raises(dr.DRError):
+            dr.dr_mfma_probe(ctx, wg, it, False, sink)
