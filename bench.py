@@ -267,26 +267,28 @@ def main():
     # MFMA-only loops on this device: the matrix cores with constant and with random register operands (same shader
     # clock probe running beside them).  The roofline denominator stays the published peak; these say how much of
     # it the device can sustain at all.
-    def mfma_only(random_operands):
+    def mfma_only(shape, random_operands):
         sink = torch.zeros(1, dtype=torch.float32, device=dev)
         clk = torch.zeros(2, dtype=torch.int64, device=dev)
         side = torch.cuda.Stream()
-        iters = 40000                                                    # ~10 ms per launch
-        dr.dr_mfma_probe(ctx, 512, 2000, random_operands, sink)         # warm-up
+        iters = 40000 if shape == 32 else 80000                         # ~10 ms per launch
+        dr.dr_mfma_probe(ctx, shape, 512, 2000, random_operands, sink)  # warm-up
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         flop = 0.0
-        dr.dr_mfma_probe(ctx, 512, iters, random_operands, sink)        # fills the chip before the clock window opens
+        dr.dr_mfma_probe(ctx, shape, 512, iters, random_operands, sink)  # fills the chip before the clock window opens
         dr.dr_clock_probe(ctx, 40000, clk, stream=side)
         e0.record()
         for _ in range(6):
-            flop += dr.dr_mfma_probe(ctx, 512, iters, random_operands, sink)
+            flop += dr.dr_mfma_probe(ctx, shape, 512, iters, random_operands, sink)
         e1.record()
         torch.cuda.synchronize()
         ticks, ref = (int(v) for v in clk.tolist())
         return {"tflops": round(flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1), "clock_mhz": round(100.0 * ticks / max(ref, 1), 1)}
-    result["mfma_only"] = {"constant_operands": mfma_only(False), "random_operands": mfma_only(True)}
-    result["roofline"]["frac_of_measured_mfma_only_random"] = round(eff_tflops / result["mfma_only"]["random_operands"]["tflops"], 4)
+    result["mfma_only"] = {"32x32x16": {"constant_operands": mfma_only(32, False), "random_operands": mfma_only(32, True)},
+                           "16x16x32": {"constant_operands": mfma_only(16, False), "random_operands": mfma_only(16, True)}}
+    result["roofline"]["frac_of_measured_mfma_only_random"] = round(
+        eff_tflops / result["mfma_only"]["32x32x16"]["random_operands"]["tflops"], 4)
     # The scoring and mask stages are HBM/latency bound; with fused-head scoring (2 of 40 heads) they move only a few
     # MB, so their bandwidth is shown on the per-head variant (head_fuse = 0: every head scored, one mask per head).
     def timed(fn, iters=20):

@@ -210,13 +210,14 @@ dr_status dr_clock_probe(dr_ctx* ctx, uint64_t window_us, uint64_t* out, void* s
 
 /* Measurement aid (not a step of the method): an MFMA-only loop, to price the attention kernel against what the
  * matrix cores of this device sustain rather than against the data-sheet peak alone.  Enqueues `workgroups`
- * workgroups of 4 wavefronts, each issuing iters * 8 v_mfma_f32_32x32x16_bf16 (32768 flop each; iters a multiple
- * of 8) on register
- * operands: one repeated value (random_operands = 0) or pseudo-random bf16 numbers in [-1, 1) (1; the switching
- * activity of real data).  `sink` is a device float the kernel may write; *flop (host, optional) receives the flop
- * count of the launch.  The caller times the launch with events on `stream`.  Errors: DR_ERR_INVALID_ARG. */
-dr_status dr_mfma_probe(dr_ctx* ctx, int32_t workgroups, int32_t iters, int32_t random_operands, float* sink,
-                        double* flop, void* stream);
+ * workgroups of 4 wavefronts, each issuing iters * 8 matrix instructions (iters a multiple of 8) on register
+ * operands and eight independent accumulators: shape 32 = v_mfma_f32_32x32x16_bf16 (32768 flop each), shape 16 =
+ * v_mfma_f32_16x16x32_bf16 (16384 flop each).  Operands are one repeated value (random_operands = 0) or
+ * pseudo-random bf16 numbers in [-1, 1) (1; the switching activity of real data).  `sink` is a device float the
+ * kernel may write; *flop (host, optional) receives the flop count of the launch.  The caller times the launch
+ * with events on `stream`.  Errors: DR_ERR_INVALID_ARG. */
+dr_status dr_mfma_probe(dr_ctx* ctx, int32_t shape, int32_t workgroups, int32_t iters, int32_t random_operands,
+                        float* sink, double* flop, void* stream);
 
 /* Library version string, e.g. "dynamicrad-gfx950 0.2". */
 const char* dr_version(void);

@@ -73,7 +73,7 @@ def load_library():
     lib.dr_build_mask.argtypes = [vp, shp, i32, f64, f64, mpp, vp, vp, vp, i64, vp, vp]
     lib.dr_sparse_attn_fwd.argtypes = [vp, shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.dr_clock_probe.argtypes = [vp, C.c_uint64, vp, vp]
-    lib.dr_mfma_probe.argtypes = [vp, i32, i32, i32, vp, C.POINTER(f64), vp]
+    lib.dr_mfma_probe.argtypes = [vp, i32, i32, i32, i32, vp, C.POINTER(f64), vp]
     for name in ("dr_clock_probe", "dr_mfma_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
                  "dr_sparse_attn_fwd"):
         getattr(lib, name).restype = C.c_int
@@ -170,9 +170,10 @@ def dr_clock_probe(ctx: Context, window_us: int, out, stream=None):
     ctx.check(ctx._lib.dr_clock_probe(ctx._h, int(window_us), _ptr(out), _stream(stream)))
 
 
-def dr_mfma_probe(ctx: Context, workgroups: int, iters: int, random_operands: bool, sink, stream=None) -> float:
-    """Enqueue the MFMA-only loop; returns the flop count of the launch (time it with events on the stream)."""
+def dr_mfma_probe(ctx: Context, shape: int, workgroups: int, iters: int, random_operands: bool, sink,
+                  stream=None) -> float:
+    """Enqueue the MFMA-only loop (shape 32: 32x32x16, 16: 16x16x32); returns the flop count of the launch."""
     flop = C.c_double(0.0)
-    ctx.check(ctx._lib.dr_mfma_probe(ctx._h, int(workgroups), int(iters), 1 if random_operands else 0, _ptr(sink),
-                                     C.byref(flop), _stream(stream)))
+    ctx.check(ctx._lib.dr_mfma_probe(ctx._h, int(shape), int(workgroups), int(iters), 1 if random_operands else 0,
+                                     _ptr(sink), C.byref(flop), _stream(stream)))
     return flop.value

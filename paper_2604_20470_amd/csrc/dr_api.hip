@@ -363,15 +363,16 @@ dr_status dr_clock_probe(dr_ctx* ctx, uint64_t window_us, uint64_t* out, void* s
     return DR_OK;
 }
 
-dr_status dr_mfma_probe(dr_ctx* ctx, int32_t workgroups, int32_t iters, int32_t random_operands, float* sink,
-                        double* flop, void* stream) {
+dr_status dr_mfma_probe(dr_ctx* ctx, int32_t shape, int32_t workgroups, int32_t iters, int32_t random_operands,
+                        float* sink, double* flop, void* stream) {
     if (!ctx) return DR_ERR_INVALID_ARG;
     if (!sink) return fail(ctx, DR_ERR_INVALID_ARG, "NULL sink pointer");
+    if (shape != 32 && shape != 16) return fail(ctx, DR_ERR_INVALID_ARG, "shape must be 32 (32x32x16) or 16 (16x16x32)");
     if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || iters > (1 << 24) || (iters & 7))
         return fail(ctx, DR_ERR_INVALID_ARG, "workgroups must be 1 .. 2^20 and iters a multiple of 8 in 8 .. 2^24");
     DeviceGuard g(ctx->device);
-    DR_HIP(ctx, launch_mfma_probe(workgroups, iters, random_operands ? 1 : 0, sink, (hipStream_t)stream));
-    if (flop) *flop = (double)workgroups * 4.0 * (double)iters * 8.0 * 32768.0;
+    DR_HIP(ctx, launch_mfma_probe(shape, workgroups, iters, random_operands ? 1 : 0, sink, (hipStream_t)stream));
+    if (flop) *flop = (double)workgroups * 4.0 * (double)iters * 8.0 * (shape == 32 ? 32768.0 : 16384.0);
     return DR_OK;
 }
 

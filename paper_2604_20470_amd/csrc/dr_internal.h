@@ -83,7 +83,7 @@ bool attn_mfma_small_supported(const AttnArgs& a);
 // ---- measurement aid ---------------------------------------------------------------------
 // out[0] = shader-clock ticks, out[1] = 100 MHz ticks elapsed over a window of window_ticks (100 MHz units).
 hipError_t launch_clock_probe(unsigned long long window_ticks, unsigned long long* out, hipStream_t s);
-// MFMA-only loop: workgroups x 4 waves x iters x 8 matrix instructions of 32768 flop each.
-hipError_t launch_mfma_probe(int workgroups, int iters, int random_operands, float* sink, hipStream_t s);
+// MFMA-only loop: workgroups x 4 waves x iters x 8 matrix instructions; shape 32 (32x32x16) or 16 (16x16x32).
+hipError_t launch_mfma_probe(int shape, int workgroups, int iters, int random_operands, float* sink, hipStream_t s);
 
 }  // namespace dr

@@ -24,12 +24,15 @@ __global__ __launch_bounds__(64) void k_clock_probe(unsigned long long window_ti
 }
 
 // Measurement aid: what the matrix cores sustain with nothing else going on.  Every wavefront keeps eight A and eight
-// B fragments in registers and issues v_mfma_f32_32x32x16_bf16 on four independent accumulators; the fragments are
+// B fragments in registers and issues matrix instructions on eight independent accumulators; the fragments are
 // either one repeated value (little switching activity) or pseudo-random bf16 numbers in [-1, 1) (the activity of
-// real operands).  8 * 32768 flop per wavefront and iteration.
+// real operands).  SHAPE 32: v_mfma_f32_32x32x16_bf16 (32768 flop), SHAPE 16: v_mfma_f32_16x16x32_bf16 (16384 flop);
+// 8 instructions per wavefront and iteration.
 typedef __bf16 pv8bf __attribute__((ext_vector_type(8)));
 typedef float pv16f __attribute__((ext_vector_type(16)));
+typedef float pv4f __attribute__((ext_vector_type(4)));
 
+template <int SHAPE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_mfma_probe(int iters, int random_operands,
                                                                                                 float* sink) {
     pv8bf a[8], b[8];
@@ -43,26 +46,42 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             const float w = random_operands ? ((x & 0xffff) / 32768.0f - 1.0f) : 0.5f;
             b[f][i] = (__bf16)w;
         }
-    pv16f acc[4];
-    for (int c = 0; c < 4; ++c)
-        for (int j = 0; j < 16; ++j) acc[c][j] = 0.f;
-    for (int it = 0; it < iters; it += 8) {          // iters is a multiple of 8 (checked on the host)
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-#pragma unroll
-            for (int f = 0; f < 8; ++f)
-                acc[f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], b[(f + j) & 7], acc[f & 3], 0, 0, 0);
-    }
     float t = 0.f;
-    for (int c = 0; c < 4; ++c)
-        for (int j = 0; j < 16; ++j) t += acc[c][j];
+    if (SHAPE == 32) {
+        pv16f acc[8];
+        for (int c = 0; c < 8; ++c)
+            for (int j = 0; j < 16; ++j) acc[c][j] = 0.f;
+        for (int it = 0; it < iters; it += 8) {          // iters is a multiple of 8 (checked on the host)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int f = 0; f < 8; ++f)
+                    acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[f], b[(f + j) & 7], acc[f], 0, 0, 0);
+        }
+        for (int c = 0; c < 8; ++c)
+            for (int j = 0; j < 16; ++j) t += acc[c][j];
+    } else {
+        pv4f acc[8];
+        for (int c = 0; c < 8; ++c)
+            for (int j = 0; j < 4; ++j) acc[c][j] = 0.f;
+        for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int f = 0; f < 8; ++f)
+                    acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[f], b[(f + j) & 7], acc[f], 0, 0, 0);
+        }
+        for (int c = 0; c < 8; ++c)
+            for (int j = 0; j < 4; ++j) t += acc[c][j];
+    }
     if (t == 1.2345e-30f) sink[0] = t;                                      // keeps the loop alive
 }
 
 }  // namespace
 
-hipError_t launch_mfma_probe(int workgroups, int iters, int random_operands, float* sink, hipStream_t s) {
-    hipLaunchKernelGGL(k_mfma_probe, dim3(workgroups), dim3(256), 0, s, iters, random_operands, sink);
+hipError_t launch_mfma_probe(int shape, int workgroups, int iters, int random_operands, float* sink, hipStream_t s) {
+    if (shape == 32) hipLaunchKernelGGL(k_mfma_probe<32>, dim3(workgroups), dim3(256), 0, s, iters, random_operands, sink);
+    else hipLaunchKernelGGL(k_mfma_probe<16>, dim3(workgroups), dim3(256), 0, s, iters, random_operands, sink);
     return hipGetLastError();
 }
 

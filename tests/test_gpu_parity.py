@@ -429,9 +429,9 @@ def test_maximum_frame_count_and_one_past_it():
 def test_mfma_probe_runs_and_checks_its_arguments():
     ctx = dr.Context(0)
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
-    flop = dr.dr_mfma_probe(ctx, 8, 16, True, sink)
+    assert dr.dr_mfma_probe(ctx, 32, 8, 16, True, sink) == 8 * 4 * 16 * 8 * 32768.0
+    assert dr.dr_mfma_probe(ctx, 16, 8, 16, False, sink) == 8 * 4 * 16 * 8 * 16384.0
     torch.cuda.synchronize()
-    assert flop == 8 * 4 * 16 * 8 * 32768.0
-    for wg, it in ((0, 16), (8, 0), (8, 12)):
+    for shape, wg, it in ((32, 0, 16), (32, 8, 0), (32, 8, 12), (8, 8, 16)):
         with pytest.raises(dr.DRError):
-            dr.dr_mfma_probe(ctx, wg, it, False, sink)
+            dr.dr_mfma_probe(ctx, shape, wg, it, False, sink)
