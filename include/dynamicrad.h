@@ -190,6 +190,11 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
  * block size; fp32 inputs, and bf16 inputs with d = 64, are computed in fp32 throughout.
  * Out-of-range key-block indices are clamped to [0, Sb) (memory safety), not reported; a row
  * whose list is not ascending is still summed correctly (softmax does not depend on the order).
+ * A key block listed twice in one row is outside the contract (block sizes 32 and 64 count it
+ * once, block size 128 once per listing).  For block sizes 32 and 64 the call first merges
+ * the rows of each group of 128 query tokens into one key-block list, in context-owned device
+ * scratch of the size of the colidx arrays it is given (B * mask_heads * colidx_stride
+ * entries), grown on demand: DR_ERR_NOMEM if that allocation fails.
  * Argument errors (NULL or misaligned pointers, strides, mask_heads) are rejected on the host
  * before any launch; the call itself is asynchronous on `stream`.
  */

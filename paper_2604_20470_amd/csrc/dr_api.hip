@@ -21,6 +21,10 @@ struct dr_ctx {
     uint32_t* keepbits = nullptr;
     int32_t* counts = nullptr;
     size_t keep_bytes = 0, count_bytes = 0;
+    // stage (c) scratch (block sizes 32 / 64): merged key-block lists per 128-row group
+    int32_t* gcol = nullptr;
+    int32_t* gcount = nullptr;
+    size_t gcol_bytes = 0, gcount_bytes = 0;
     // cached candidate geometry
     uint8_t* class_map = nullptr;
     int32_t* row_sel = nullptr;
@@ -213,7 +217,8 @@ void dr_destroy(dr_ctx* ctx) {
     if (!ctx) return;
     {
         DeviceGuard g(ctx->device);
-        void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->row_sel, ctx->totals};
+        void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->row_sel, ctx->totals, ctx->gcol,
+                        ctx->gcount};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
     }
@@ -348,9 +353,20 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
     a.Sb = (shape->N + shape->Bs - 1) / shape->Bs;
     a.bf16 = shape->dtype == DR_BF16;
     hipStream_t s = (hipStream_t)stream;
-    if (attn_mfma_supported(a)) DR_HIP(ctx, launch_attn_mfma(a, s));
-    else if (attn_mfma_small_supported(a)) DR_HIP(ctx, launch_attn_mfma_small(a, s));
-    else DR_HIP(ctx, launch_attn_generic(a, s));
+    if (attn_mfma_supported(a)) {
+        DR_HIP(ctx, launch_attn_mfma(a, s));
+    } else if (attn_mfma_small_supported(a)) {
+        if (a.Sb >= (1 << 28)) return fail(ctx, DR_ERR_UNSUPPORTED, "too many blocks for the packed group lists");
+        const size_t groups = (size_t)(shape->N + 127) / 128;
+        dr_status gst;
+        if ((gst = grow(ctx, (void**)&ctx->gcol, &ctx->gcol_bytes, (size_t)shape->B * mask_heads * (size_t)colidx_stride * 4 + 4)) != DR_OK) return gst;
+        if ((gst = grow(ctx, (void**)&ctx->gcount, &ctx->gcount_bytes, (size_t)shape->B * mask_heads * groups * 4)) != DR_OK) return gst;
+        a.gcol = ctx->gcol;
+        a.gcount = ctx->gcount;
+        DR_HIP(ctx, launch_attn_mfma_small(a, s));
+    } else {
+        DR_HIP(ctx, launch_attn_generic(a, s));
+    }
     return DR_OK;
 }
 

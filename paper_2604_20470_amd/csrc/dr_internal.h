@@ -70,6 +70,9 @@ struct AttnArgs {
     TensorDesc td;
     int32_t Bs, Sb;
     int32_t bf16;
+    // scratch of the small-block MFMA path: per 128-row group the merged key-block list (laid out like colidx) and its length
+    int32_t* gcol;               // [B, mask_heads, colidx_stride]
+    int32_t* gcount;             // [B, mask_heads, ceil(N / 128)]
 };
 // Any d in {64,128}, Bs in {32,64,128}, f32 or bf16 storage; arithmetic in fp32 on the vector ALUs.
 hipError_t launch_attn_generic(const AttnArgs& a, hipStream_t s);

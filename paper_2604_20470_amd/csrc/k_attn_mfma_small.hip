@@ -6,6 +6,9 @@
 // registers), but a workgroup's 128 query rows now span 128 / Bs query blocks, each with its own row of the CSR.
 // The workgroup walks the ascending UNION of those rows: a key block is fetched into LDS once and every wavefront
 // whose query block lists it multiplies against it; the others only take part in the loads and the barrier.
+// The union is formed beforehand by k_group_union (one small launch per call): per 128-row group one list of
+// packed entries, key block in the low 28 bits and the set of rows listing it in the top 4, so that the attention
+// kernel follows a single list through a single register window, like the Bs = 128 kernel.
 // Neighbouring query blocks share most of their key blocks (the never-pruned zone of a frame), so the gather
 // traffic per useful flop stays close to that of Bs = 128 instead of growing 4x or 16x.
 //   Bs = 64: a chunk is one key block; wavefronts 0-1 and 2-3 follow their own row.
@@ -113,9 +116,11 @@ struct State {
     float l_part;
 };
 
+// The swizzles are xors on the 16-byte piece index and the LDS block is 1 KB aligned, so the address of contraction
+// step ks / channel block db is the base with ks << 5 / db << 6 xor-ed in: two registers instead of twelve.
 struct ReadPlan {
-    uint32_t k_addr[8];
-    uint32_t v_addr[4];
+    uint32_t k_base;      // this lane's 16 bytes of key row (lane & 31), step 0, stage 0
+    uint32_t v_base;      // this lane's 8 bytes of the transposing read for channel block 0, stage 0
 };
 
 // One chunk for one wavefront.  MBM = 3: both 32-key halves of the tile are this wavefront's; MBM = 1: one half, the
@@ -130,6 +135,8 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
     constexpr uint32_t kK = STAGE * kStageBytes, kV = STAGE * kStageBytes + kTileBytes;
     constexpr int MB0 = (MBM & 1) ? 0 : 1, MB1 = (MBM & 2) ? 2 : 1;     // active key sub-blocks: MB0 .. MB1 - 1
 
+    uint32_t k_base = rd.k_base, v_base = rd.v_base;
+    asm volatile("" : "+v"(k_base), "+v"(v_base));   // the per-step addresses are formed here, not kept in registers across chunks
     // Register budget: the logit fragments are read in two batches of four contraction steps and the V^T fragments
     // one key sub-block at a time (the second one into the registers the logits vacate), so that the variants
     // of this body and the union walk fit the 256 registers of a wave without spilling into the loop.
@@ -139,8 +146,8 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
                 union { struct { v4s a, b; } s2; v8bf v; } u;
-                u.s2.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + kV + sel_off + (mb * 32 + t * 16) * kRowBytes));
-                u.s2.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + kV + sel_off + (mb * 32 + t * 16 + 8) * kRowBytes));
+                u.s2.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)((v_base ^ (db << 6)) + kV + sel_off + (mb * 32 + t * 16) * kRowBytes));
+                u.s2.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)((v_base ^ (db << 6)) + kV + sel_off + (mb * 32 + t * 16 + 8) * kRowBytes));
                 dst[t][db] = u.v;
             }
     };
@@ -155,7 +162,7 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
         for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
             for (int mb = MB0; mb < MB1; ++mb)
-                kf[mb][k4] = *(lds_v8)(uintptr_t)(rd.k_addr[batch * 4 + k4] + kK + sel_off + mb * 32 * kRowBytes);
+                kf[mb][k4] = *(lds_v8)(uintptr_t)((k_base ^ ((batch * 4 + k4) << 5)) + kK + sel_off + mb * 32 * kRowBytes);
         __builtin_amdgcn_sched_barrier(0);
         if (batch == 0) {
             issue();
@@ -279,8 +286,6 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
     const char* Vh = reinterpret_cast<const char*>(a.V) + head_off;
     const int mh = (a.mask_heads == 1) ? 0 : h;
     const int32_t* rp = a.rowptr + ((int64_t)b * a.mask_heads + mh) * (a.Sb + 1);
-    const int32_t* ci = a.colidx + ((int64_t)b * a.mask_heads + mh) * a.colidx_stride;
-
     const float cs = 1.4426950408889634f / sqrtf((float)kD);
     const int q_wave0 = qg * kRowsPerGroup + wave * 32;
     v8bf qf[8];
@@ -305,16 +310,12 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
     lp.m0_k = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
 
     ReadPlan rd;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) rd.k_addr[ks] = lds0 + l32 * kRowBytes + (((ks * 2 + half) ^ (l32 & 15)) << 4);
+    rd.k_base = lds0 + l32 * kRowBytes + ((half ^ (l32 & 15)) << 4);
     {
         const int v_e = (lane & 15) >> 2, v_c = lane & 3, v_grp = (lane >> 4) & 1;
         const int r0 = half * 4 + v_e;
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            const int piece = db * 4 + v_grp * 2 + (v_c >> 1);
-            rd.v_addr[db] = lds0 + r0 * kRowBytes + ((piece ^ (v_e << 2)) << 4) + (v_c & 1) * 8;
-        }
+        const int piece = v_grp * 2 + (v_c >> 1);
+        rd.v_base = lds0 + r0 * kRowBytes + ((piece ^ (v_e << 2)) << 4) + (v_c & 1) * 8;
     }
 
     State st;
@@ -326,41 +327,27 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) st.o[db][j] = 0.f;
 
-    // ---- the L rows of the CSR this workgroup follows, each through a 64-entry register window ----
-    int beg[L], cnt[L], pos[L], win[L];
-#pragma unroll
-    for (int l = 0; l < L; ++l) {
-        const int qb = qg * L + l;
-        beg[l] = (qb < a.Sb) ? __builtin_amdgcn_readfirstlane(rp[qb]) : 0;
-        cnt[l] = (qb < a.Sb) ? __builtin_amdgcn_readfirstlane(rp[qb + 1]) - beg[l] : 0;
-        pos[l] = 0;
-        win[l] = (cnt[l] > 0) ? ci[beg[l] + min(lane, cnt[l] - 1)] : 0;
-    }
+    // ---- the group's pre-merged list: entry = key block | (rows listing it) << 28, through a 64-entry register window ----
+    const int gmask = (a.mask_heads == 1) ? 0 : h;
+    const int64_t gid = ((int64_t)b * a.mask_heads + gmask) * groups + qg;
+    const int first_row = min(qg * L, a.Sb);
+    const int32_t* gl = a.gcol + ((int64_t)b * a.mask_heads + gmask) * a.colidx_stride + __builtin_amdgcn_readfirstlane(rp[first_row]);
+    const int cnt = __builtin_amdgcn_readfirstlane(a.gcount[gid]);
+    int pos = 0;
+    int win = (cnt > 0) ? gl[min(lane, cnt - 1)] : 0;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
-#pragma unroll
-    for (int l = 0; l < L; ++l) asm volatile("" : "+v"(win[l]));
-    // next entry of the ascending union: its key block and the rows that list it (clamped: memory safety)
+    asm volatile("" : "+v"(win));
     auto next_entry = [&](int& kb, uint32_t& rows) {
-        int head[L];
-        kb = kNoBlock;
-#pragma unroll
-        for (int l = 0; l < L; ++l) {
-            head[l] = (pos[l] < cnt[l]) ? min(max(__builtin_amdgcn_readlane(win[l], pos[l] & 63), 0), a.Sb - 1) : kNoBlock;
-            kb = min(kb, head[l]);
+        if (pos >= cnt) { kb = kNoBlock; rows = 0; return; }
+        const uint32_t e = (uint32_t)__builtin_amdgcn_readlane(win, pos & 63);
+        kb = min((int)(e & 0x0fffffffu), a.Sb - 1);
+        rows = e >> 28;
+        ++pos;
+        if ((pos & 63) == 0 && pos < cnt) {
+            win = gl[min(pos + lane, cnt - 1)];
+            asm volatile("" : "+v"(win));
         }
-        rows = 0;
-        if (kb == kNoBlock) return;
-#pragma unroll
-        for (int l = 0; l < L; ++l)
-            if (head[l] == kb) {
-                rows |= 1u << l;
-                ++pos[l];
-                if ((pos[l] & 63) == 0 && pos[l] < cnt[l]) {
-                    win[l] = ci[beg[l] + min(pos[l] + lane, cnt[l] - 1)];
-                    asm volatile("" : "+v"(win[l]));
-                }
-            }
     };
     auto fetch = [&]() {
         Chunk c;
@@ -447,13 +434,84 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
     }
 }
 
-// Bs = 64 fits two workgroups per CU (256 registers per wave).  The Bs = 32 walk keeps four CSR rows in flight and
-// does not fit that budget without spilling into the loop (and a spill reload would wait on the tile loads in
-// flight), so it runs one workgroup per CU with the larger register file.
+// Pre-pass: the ascending union of the L = 128 / Bs CSR rows of every 128-row group, one entry per key block with the
+// set of rows that list it in the top four bits.  A group's entries are written at the colidx offset of its first row
+// (the union is never longer than the rows together), its length to gcount.  Indices are clamped to [0, Sb); an
+// index listed twice in a row counts once.
+// grid: (groups, mask_heads, B).  LDS: L * words presence bitmaps.
+template <int BS>
+__global__ __launch_bounds__(256) void k_group_union(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                                     int64_t colidx_stride, int Sb, int groups,
+                                                     int32_t* __restrict__ gcol, int32_t* __restrict__ gcount) {
+    constexpr int L = kRowsPerGroup / BS;
+    extern __shared__ uint32_t pres[];                 // [L][words]
+    __shared__ int s_wave[4];
+    const int g = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
+    const int masks = gridDim.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int words = (Sb + 31) / 32;
+    const int64_t mask_id = (int64_t)b * masks + m;
+    const int32_t* rp = rowptr + mask_id * (Sb + 1);
+    const int32_t* ci = colidx + mask_id * colidx_stride;
+    for (int i = tid; i < L * words; i += 256) pres[i] = 0u;
+    __syncthreads();
+    const int row0 = min(g * L, Sb), row1 = min(g * L + L, Sb);
+    for (int l = 0; l < row1 - row0; ++l) {
+        const int beg = rp[row0 + l], end = rp[row0 + l + 1];
+        for (int i = beg + tid; i < end; i += 256) {
+            const int kb = min(max(ci[i], 0), Sb - 1);
+            atomicOr(&pres[l * words + (kb >> 5)], 1u << (kb & 31));
+        }
+    }
+    __syncthreads();
+    const int64_t off0 = rp[row0];
+    int32_t* out = gcol + mask_id * colidx_stride + off0;
+    const int64_t room = colidx_stride - off0;             // a well-formed CSR never needs more; a malformed one is cut
+    int base = 0;
+    for (int w0 = 0; w0 < words; w0 += 256) {
+        const int wi = w0 + tid;
+        uint32_t any = 0u, r[L];
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            r[l] = (wi < words) ? pres[l * words + wi] : 0u;
+            any |= r[l];
+        }
+        const int c = __popc(any);
+        int incl = c;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int wave_base = 0, total = 0;
+        for (int i = 0; i < 4; ++i) {
+            if (i < wave) wave_base += s_wave[i];
+            total += s_wave[i];
+        }
+        int posn = base + wave_base + incl - c;
+        uint32_t bits = any;
+        while (bits) {
+            const int bit = __ffs(bits) - 1;
+            bits &= bits - 1;
+            uint32_t rows = 0;
+#pragma unroll
+            for (int l = 0; l < L; ++l) rows |= ((r[l] >> bit) & 1u) << l;
+            if (posn < room) out[posn] = (int32_t)((uint32_t)(wi * 32 + bit) | (rows << 28));
+            ++posn;
+        }
+        base += total;
+        __syncthreads();
+    }
+    if (tid == 0) gcount[mask_id * groups + g] = (int)max((int64_t)0, min((int64_t)base, room));
+}
+
+// Both block sizes fit two workgroups per CU (256 registers per wave) without spilling into the loop; a spill reload
+// there would wait on the tile loads in flight.
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma_bs64(AttnArgs a) {
     attn_small_body<64>(a);
 }
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_bs32(AttnArgs a) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma_bs32(AttnArgs a) {
     attn_small_body<32>(a);
 }
 
@@ -463,6 +521,19 @@ hipError_t launch_small(Kern kern, const AttnArgs& a, hipStream_t s) {
                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr != hipSuccess) return attr;
     const int groups = (a.td.N + kRowsPerGroup - 1) / kRowsPerGroup;
+    {
+        const int L = kRowsPerGroup / a.Bs;
+        const size_t lds = (size_t)L * ((a.Sb + 31) / 32) * 4;
+        const dim3 grid(groups, a.mask_heads, a.td.B);
+        if (a.Bs == 32)
+            hipLaunchKernelGGL(k_group_union<32>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups,
+                               a.gcol, a.gcount);
+        else
+            hipLaunchKernelGGL(k_group_union<64>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups,
+                               a.gcol, a.gcount);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     const int total = groups * a.td.H * a.td.B;
     const int grid = (total + 7) / 8 * 8;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
