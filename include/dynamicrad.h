@@ -153,7 +153,9 @@ dr_status dr_block_scores(dr_ctx* ctx, const dr_shape* shape, const void* Q, con
  *             fmix32(fmix32(seed ^ fmix32(qb)) + kb), fmix32 = MurmurHash3's finaliser;
  *             the max(1, floor(n * ratio)) smallest keys are kept (ties by lower index);
  *             with params->ratio_far >= 0 NEAR and FAR are sampled separately.  The mask
- *             depends on the geometry and the seed only, so a caller can build it once.
+ *             depends on the geometry, the ratios and the seed only (the same for every b
+ *             and every mask head): the context keeps the selection of the last such
+ *             call, and a call that repeats it only writes the CSR out.
  * Output is CSR per mask: rowptr[b, m, 0..Sb] (rowptr[..,0] = 0) and strictly
  * ascending key-block indices in colidx[b, m, rowptr[qb] .. rowptr[qb+1]).
  *   mode           dr_mode

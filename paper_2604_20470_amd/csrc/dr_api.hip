@@ -25,6 +25,12 @@ struct dr_ctx {
     int32_t* gcol = nullptr;
     int32_t* gcount = nullptr;
     size_t gcol_bytes = 0, gcount_bytes = 0;
+    // cached selection of the uniform rule (it depends on geometry, ratios and seed only): one mask of Sb rows
+    uint32_t* uni_keep = nullptr;
+    int32_t* uni_counts = nullptr;
+    size_t uni_keep_bytes = 0, uni_count_bytes = 0;
+    bool uni_valid = false;
+    struct UniKey { double ratio, ratio_far; uint32_t seed; int32_t pad; } uni_key{};
     // cached candidate geometry
     uint8_t* class_map = nullptr;
     int32_t* row_sel = nullptr;
@@ -168,6 +174,7 @@ dr_status ensure_geometry(dr_ctx* ctx, const dr_shape* s, double lambda, const d
     dr_ctx::Key k{s->N, s->Nf, Nt, s->Bs, p->gamma, lambda, p->theta_c, p->theta_m};
     if (ctx->geom_valid && std::memcmp(&k, &ctx->key, sizeof k) == 0) return DR_OK;
     ctx->geom_valid = false;
+    ctx->uni_valid = false;
     const int Sb = (s->N + s->Bs - 1) / s->Bs;
     dr_status st;
     if ((st = grow(ctx, (void**)&ctx->class_map, &ctx->class_bytes, (size_t)Sb * Sb)) != DR_OK) return st;
@@ -218,7 +225,7 @@ void dr_destroy(dr_ctx* ctx) {
     {
         DeviceGuard g(ctx->device);
         void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->row_sel, ctx->totals, ctx->gcol,
-                        ctx->gcount};
+                        ctx->gcount, ctx->uni_keep, ctx->uni_counts};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
     }
@@ -310,8 +317,17 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
         return fail(ctx, DR_ERR_UNSUPPORTED, "%d selectable blocks in a row exceed %d", ctx->max_sel, kMaxSelectablePerRow);
     const size_t rows = (size_t)shape->B * masks * Sb;
     const size_t words = (Sb + 31) / 32;
-    if ((st = grow(ctx, (void**)&ctx->keepbits, &ctx->keep_bytes, rows * words * 4)) != DR_OK) return st;
-    if ((st = grow(ctx, (void**)&ctx->counts, &ctx->count_bytes, rows * 4)) != DR_OK) return st;
+    const bool uniform = mode == DR_MODE_UNIFORM_RATIO;
+    if (uniform) {
+        // The sample is the same for every batch element and head and for every call with this geometry, these
+        // ratios and this seed (paper: the static mask is computed once, "Selector Efficiency" appendix): select once
+        // for one mask, keep it in the context, and only write it out per call.
+        if ((st = grow(ctx, (void**)&ctx->uni_keep, &ctx->uni_keep_bytes, (size_t)Sb * words * 4)) != DR_OK) return st;
+        if ((st = grow(ctx, (void**)&ctx->uni_counts, &ctx->uni_count_bytes, (size_t)Sb * 4)) != DR_OK) return st;
+    } else {
+        if ((st = grow(ctx, (void**)&ctx->keepbits, &ctx->keep_bytes, rows * words * 4)) != DR_OK) return st;
+        if ((st = grow(ctx, (void**)&ctx->counts, &ctx->count_bytes, rows * 4)) != DR_OK) return st;
+    }
     SelectArgs a{};
     a.mode = mode;
     a.two_ratio = ((mode == DR_MODE_STATIC_RATIO || mode == DR_MODE_UNIFORM_RATIO) && p->ratio_far > 0.0) ? 1 : 0;
@@ -325,11 +341,23 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
     a.tau_far = p->has_tau_far ? p->tau_far : ratio_or_tau;
     a.seed = p->seed;
     a.N = shape->N; a.Nt = shape->Hg * shape->Wg; a.Nf = shape->Nf; a.Bs = shape->Bs;
+    if (uniform) {
+        dr_ctx::UniKey uk{};
+        uk.ratio = ratio_or_tau; uk.ratio_far = p->ratio_far; uk.seed = p->seed;
+        if (!ctx->uni_valid || std::memcmp(&uk, &ctx->uni_key, sizeof uk) != 0) {
+            ctx->uni_valid = false;
+            DR_HIP(ctx, launch_select(ctx->class_map, nullptr, 1, 1, Sb, a, ctx->uni_keep, ctx->uni_counts, s));
+            std::memcpy(&ctx->uni_key, &uk, sizeof uk);
+            ctx->uni_valid = true;
+        }
+        DR_HIP(ctx, launch_emit(ctx->uni_keep, ctx->uni_counts, shape->B, masks, Sb, true, rowptr, colidx, colidx_capacity, nnz, s));
+        return DR_OK;
+    }
     if (mode == DR_MODE_ZSCORE_THRESHOLD)
         DR_HIP(ctx, launch_select_zscore(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
     else
         DR_HIP(ctx, launch_select(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
-    DR_HIP(ctx, launch_emit(ctx->keepbits, ctx->counts, shape->B, masks, Sb, rowptr, colidx, colidx_capacity, nnz, s));
+    DR_HIP(ctx, launch_emit(ctx->keepbits, ctx->counts, shape->B, masks, Sb, false, rowptr, colidx, colidx_capacity, nnz, s));
     return DR_OK;
 }
 

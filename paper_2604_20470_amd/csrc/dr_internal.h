@@ -55,7 +55,7 @@ hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, i
 // z-score mode (paper Eqs. 10-11 at block level); same outputs as launch_select
 hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
                                 const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
-hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb,
+hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb, bool shared,
                        int32_t* rowptr, int32_t* colidx, int64_t capacity, int64_t* nnz, hipStream_t s);
 
 // ---- stage (c) -------------------------------------------------------------------------

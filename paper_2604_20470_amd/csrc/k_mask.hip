@@ -294,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void k_select_zscore(const uint8_t* __res
 
 // grid: (Sb, masks, B)
 __global__ __launch_bounds__(kThreads) void k_emit(const uint32_t* __restrict__ keepbits,
-                                                   const int32_t* __restrict__ counts, int masks, int Sb,
+                                                   const int32_t* __restrict__ counts, int masks, int Sb, int shared,
                                                    int32_t* __restrict__ rowptr, int32_t* __restrict__ colidx,
                                                    int64_t capacity, int64_t* __restrict__ nnz) {
     __shared__ long long s_off;
@@ -302,12 +302,13 @@ __global__ __launch_bounds__(kThreads) void k_emit(const uint32_t* __restrict__ 
     const int qb = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int64_t mask_id = (int64_t)b * masks + m;
-    const int64_t row = mask_id * Sb + qb;
+    const int64_t src = shared ? 0 : mask_id * Sb;      // shared: one selection (Sb rows) serves every (b, m)
+    const int64_t row = src + qb;
     const int words = (Sb + 31) / 32;
     if (tid == 0) s_off = 0;
     __syncthreads();
     long long part = 0;
-    for (int i = tid; i < qb; i += kThreads) part += counts[mask_id * Sb + i];
+    for (int i = tid; i < qb; i += kThreads) part += counts[src + i];
     for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off);
     if (lane == 0 && part) atomicAdd((unsigned long long*)&s_off, (unsigned long long)part);
     __syncthreads();
@@ -382,9 +383,9 @@ hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, i
     return hipGetLastError();
 }
 
-hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb,
+hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb, bool shared,
                        int32_t* rowptr, int32_t* colidx, int64_t capacity, int64_t* nnz, hipStream_t s) {
-    hipLaunchKernelGGL(k_emit, dim3(Sb, masks, B), dim3(kThreads), 0, s, keepbits, counts, masks, Sb, rowptr, colidx,
+    hipLaunchKernelGGL(k_emit, dim3(Sb, masks, B), dim3(kThreads), 0, s, keepbits, counts, masks, Sb, shared ? 1 : 0, rowptr, colidx,
                        capacity, nnz);
     return hipGetLastError();
 }

@@ -66,6 +66,32 @@ def test_uniform_masks_bit_exact_and_score_free(wl):
         assert torch.equal(colidx[0, 0, :int(nnz[0, 0])], colidx2[0, 0, :int(nnz[0, 0])])
 
 
+def test_uniform_selection_cached_in_the_context_follows_every_parameter():
+    """The uniform sample is kept in the context and only written out on later calls: one context must still
+    follow a change of seed, of either ratio, of lambda (geometry) and of the mask layout (fused / per head, B > 1)."""
+    wl = tiny_case("ragged")
+    run = GpuRun(wl, params=dr.MaskParams(gamma=3.0, head_fuse=0))
+    assert run.masks == wl.H and wl.H > 1
+    steps = [dict(ratio=0.3, ratio_far=-1.0, seed=5, lam=wl.lam), dict(ratio=0.3, ratio_far=-1.0, seed=5, lam=wl.lam),
+             dict(ratio=0.3, ratio_far=-1.0, seed=6, lam=wl.lam), dict(ratio=0.6, ratio_far=-1.0, seed=6, lam=wl.lam),
+             dict(ratio=0.6, ratio_far=0.2, seed=6, lam=wl.lam), dict(ratio=0.6, ratio_far=0.2, seed=6, lam=2.0 * wl.lam),
+             dict(ratio=0.3, ratio_far=-1.0, seed=5, lam=wl.lam)]
+    for head_fuse in (0, 2):
+        for st in steps:
+            run.params = dr.MaskParams(gamma=3.0, head_fuse=head_fuse, ratio_far=st["ratio_far"], seed=st["seed"])
+            cls = oracle_class_map(wl, gamma=3.0, lam=st["lam"])
+            rowptr, colidx, nnz, cap = run.build_mask(None, "uniform", st["ratio"], lam=st["lam"])
+            shape_only = np.zeros((wl.B, run.masks, wl.Sb, wl.Sb), dtype=np.float32)
+            want = o.build_mask(shape_only, cls, "uniform", st["ratio"], ratio_far=st["ratio_far"], seed=st["seed"])
+            assert_masks_equal(rowptr, colidx, nnz, want)
+    # another rule in between uses its own scratch and does not disturb the cached sample
+    run.params = dr.MaskParams(gamma=3.0, head_fuse=2, seed=5)
+    a = run.build_mask(None, "uniform", 0.3)
+    run.build_mask(run.block_scores(), "static", 0.5)
+    b = run.build_mask(None, "uniform", 0.3)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+
+
 def test_paper_modes_feed_the_attention_stage():
     """scores -> z-score mask -> attention and uniform mask -> attention, checked like the other pipelines."""
     from test_gpu_parity import ATTN_TOL, _attention_check
