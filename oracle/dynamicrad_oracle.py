@@ -28,6 +28,12 @@ Stages, in the order of the method (paper sections in brackets):
                     seeded, score-free uniform sample of k blocks
                     [Eq. 8 with k = max(1, floor(n rho)), "deterministic seed"]
   build_mask        all rows -> CSR (rowptr, colidx)  [Algorithm 1's output M_b]
+  token_scores / select_token_links / aggregate_links / build_mask_from_tokens
+                    Algorithm 1 in its own order, for small N: the proxy score
+                    of every token pair, z-score thresholds inside each frame
+                    pair's candidate set, then the density aggregation of the
+                    kept links to blocks  [Eqs. 7, 9-11; "Density control
+                    within blocks"; Algorithm 1]
   masked_attention  softmax over exactly the keys of the kept blocks
                     [Eqs. 12-13 with epsilon -> 0]
   attention_matrix / proxy_loss   the row-normalised attention matrix under a
@@ -58,6 +64,12 @@ interpretation, listed again in the design notes):
     standard deviation are the population ones (divide by n), epsilon of
     Eq. 10 is 1e-6, and a block is kept when z >= tau (Algorithm 1 writes >=).
     All of it in fp64, sums taken one by one in ascending key-block order.
+  * token-level order (build_mask_from_tokens): statistics of a frame pair
+    are taken over its whole candidate set P(i, j) as Eq. 10 says; the sums
+    run column by column (u ascending inside a column, then the column sums
+    over v ascending), one by one in fp64; the aggregation is applied to the
+    merged link matrix block by block, and blocks touching the t <= 1 zone
+    are kept as in the block-level path.
   * uniform mode: every selectable block of a row gets the 32-bit key
     fmix32(fmix32(seed ^ fmix32(qb)) + kb) (fmix32 = the finaliser of
     MurmurHash3); the k blocks with the smallest keys are kept, equal keys by
@@ -452,6 +464,124 @@ def build_mask(scores_f32: np.ndarray, cls_map: np.ndarray, mode: str, ratio_or_
                 cols.append(kept)
                 rowptr[qb + 1] = rowptr[qb] + len(kept)
             per_b.append((rowptr, np.concatenate(cols) if cols else np.zeros(0, np.int64)))
+        out.append(per_b)
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# Algorithm 1 in its own order: token-pair selection per frame pair, then
+# aggregation of the kept links to blocks (small N only)
+# --------------------------------------------------------------------------- #
+def token_scores(Q: np.ndarray, K: np.ndarray, head_fuse: int) -> np.ndarray:
+    """Proxy score of every token pair, Eq. 9: s(p, q) = mean over the head set of Q_p . K_q / sqrt(d).
+
+    Q, K: [B, H, N, d].  head_fuse = Hf > 0: heads 0..Hf-1 averaged, one matrix per batch element;
+    0: one matrix per head.  Returns [B, masks, N, N] float64.
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    B, H, N, d = Q.shape
+    logits = np.einsum("bhpc,bhqc->bhpq", Q, K) / math.sqrt(d)
+    if head_fuse > 0:
+        return logits[:, :head_fuse].mean(axis=1, keepdims=True)
+    return logits
+
+
+def _sum_columns_then_across(x: np.ndarray) -> float:
+    """Sum of a matrix in the order both sides use: every column v is added up over u ascending, then the column
+    sums are added up over v ascending, all one by one in fp64.  (Entries outside the window are passed in as +0,
+    which leaves every partial sum as it is.)"""
+    col = np.add.accumulate(x, axis=0)[-1]          # accumulate is a strictly sequential running sum
+    return float(np.add.accumulate(col)[-1])
+
+
+def select_token_links(scores_f32: np.ndarray, N: int, Nt: int, tab: Dict[str, np.ndarray],
+                       tau_near: float, tau_far: float, eps: float = 1e-6) -> np.ndarray:
+    """Kept token links [N, N] (bool) under the dynamic-threshold rule, frame pair by frame pair (Algorithm 1).
+
+    For the ordered frame pair (i, j), t = |i - j|:
+      t <= 1                     every token pair is kept (w = Nt in Eq. 3, tau = -inf in Eq. 11);
+      t mod sf(t) != 0           nothing is kept (Eq. 6);
+      otherwise                  P(i, j) = {(u, v): |u - v| <= w(t)} (Eq. 7); mu and sigma are the mean and the
+                                 population standard deviation of the scores in P(i, j) (Eq. 10), z = (s - mu) /
+                                 (sigma + eps), and a pair is kept when z >= tau, tau = tau_near if the decay length
+                                 L(t) >= Bs else tau_far (Eq. 11); if no pair passes, the highest score of the set
+                                 is kept (first in row-major (u, v) order on ties).
+    scores_f32: [N, N] float32 (token_scores rounded once, or the GPU's own).
+    """
+    s_all = np.asarray(scores_f32)
+    assert s_all.dtype == np.float32 and s_all.shape == (N, N)
+    Nf = N // Nt
+    assert Nf * Nt == N
+    links = np.zeros((N, N), dtype=bool)
+    u = np.arange(Nt)
+    dist = np.abs(u[:, None] - u[None, :])
+    for i in range(Nf):
+        for j in range(Nf):
+            t = abs(i - j)
+            blk = (slice(i * Nt, (i + 1) * Nt), slice(j * Nt, (j + 1) * Nt))
+            if t <= 1:
+                links[blk] = True
+                continue
+            if not tab["retained"][t]:
+                continue
+            inside = dist <= int(tab["w"][t])
+            s = s_all[blk].astype(np.float64)
+            n = int(inside.sum())
+            mu = _sum_columns_then_across(np.where(inside, s, 0.0)) / n
+            dev = s - mu
+            sigma = math.sqrt(_sum_columns_then_across(np.where(inside, dev * dev, 0.0)) / n)
+            tau = tau_near if tab["cls"][t] == CLASS_NEAR else tau_far
+            keep = inside & (dev / (sigma + eps) >= tau)
+            if not keep.any():
+                best = int(np.argmax(np.where(inside, s, -np.inf)))      # first maximum in row-major order
+                keep = np.zeros_like(inside)
+                keep[best // Nt, best % Nt] = True
+            links[blk] = keep
+    return links
+
+
+def aggregate_links(links: np.ndarray, N: int, Nt: int, Bs: int, theta_c: float, theta_m: float) -> np.ndarray:
+    """Block mask [Sb, Sb] (bool) from token links ("Density control within blocks"; the last step of Algorithm 1).
+
+    Column c of block (qb, kb) is active when (#kept rows of the column) / (#valid rows) > theta_c; the block is
+    kept when (#active columns) / (#valid columns) > theta_m.  A block holding any token pair with t <= 1 is kept
+    whatever its density (the never-pruned zone, as in classify_blocks).
+    """
+    Sb = -(-N // Bs)
+    frame = np.arange(N) // Nt
+    out = np.zeros((Sb, Sb), dtype=bool)
+    for qb in range(Sb):
+        r0, r1 = _block_range(qb, Bs, N)
+        for kb in range(Sb):
+            c0, c1 = _block_range(kb, Bs, N)
+            if int(np.abs(frame[r0:r1, None] - frame[None, c0:c1]).min()) <= 1:
+                out[qb, kb] = True
+                continue
+            active = links[r0:r1, c0:c1].sum(axis=0) / float(r1 - r0) > theta_c
+            out[qb, kb] = active.sum() / float(c1 - c0) > theta_m
+    return out
+
+
+def build_mask_from_tokens(scores_f32: np.ndarray, N: int, Nt: int, Bs: int, tab: Dict[str, np.ndarray],
+                           theta_c: float, theta_m: float, tau_near: float, tau_far: Optional[float] = None
+                           ) -> List[List[Tuple[np.ndarray, np.ndarray]]]:
+    """Algorithm 1 in the paper's own order, dynamic-threshold mode: token links per frame pair
+    (select_token_links), then block aggregation (aggregate_links); CSR per (batch, mask head).
+    scores_f32: [B, masks, N, N] float32."""
+    scores_f32 = np.asarray(scores_f32)
+    assert scores_f32.dtype == np.float32
+    B, Hm = scores_f32.shape[:2]
+    Sb = -(-N // Bs)
+    out = []
+    for b in range(B):
+        per_b = []
+        for m in range(Hm):
+            links = select_token_links(scores_f32[b, m], N, Nt, tab, tau_near, tau_near if tau_far is None else tau_far)
+            keep = aggregate_links(links, N, Nt, Bs, theta_c, theta_m)
+            rowptr = np.zeros(Sb + 1, dtype=np.int64)
+            rowptr[1:] = np.cumsum(keep.sum(axis=1))
+            per_b.append((rowptr, np.nonzero(keep)[1].astype(np.int64)))
         out.append(per_b)
     return out
 
