@@ -204,6 +204,43 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
                              const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads,
                              int64_t colidx_stride, void* O, float* lse, void* stream);
 
+/*
+ * Algorithm 1 in the paper's own order, for small sequences (an evaluation aid: it shows what the block-level
+ * restatement of dr_build_mask changes).  Paper: proxy score of a token pair (Eq. 9), candidate set of a frame
+ * pair (Eq. 7), score normalisation inside it (Eq. 10), decay-state thresholds with the keep-one safeguard
+ * (Eq. 11), aggregation of the kept links to blocks ("Density control within blocks", last step of Algorithm 1).
+ *
+ * dr_token_scores: scores[b, m, p, q] = mean over the heads of mask m of Q_p . K_q / sqrt(d), fp32.
+ *   Q, K       device, dtype/strides of `shape`
+ *   head_fuse  as in dr_block_scores
+ *   scores     device, float32, contiguous [B, masks, N, N]
+ *   N <= 16384, else DR_ERR_UNSUPPORTED.
+ *
+ * dr_build_mask_tokens: for every ordered frame pair (i, j), t = |i - j|:
+ *   t <= 1: every token pair is a link; t not retained (Eq. 6): none; otherwise over the candidate set
+ *   P(i, j) = {(u, v): |u - v| <= w(t)}: mu = mean, sigma = population standard deviation of the scores,
+ *   z = (s - mu) / (sigma + 1e-6), link when z >= tau, tau = `tau_near` when the decay length L(t) >= Bs, else
+ *   params->tau_far (if has_tau_far, else tau_near); if no pair of the set passes, its highest score is a link
+ *   (first in row-major (u, v) order on ties).  Statistics in fp64 with every sum taken column by column (u
+ *   ascending inside key column v, then the column sums with v ascending), one by one, no fused multiply-add:
+ *   part of the definition, so that masks are reproducible bit for bit.
+ *   Then block (qb, kb) is kept when it holds a token pair with t <= 1, or when
+ *   #{columns c: #links in column c / #valid rows > theta_c} / #valid columns > theta_m.
+ *   token_scores  device, float32, contiguous [B, masks, N, N] (dr_token_scores' output)
+ *   rowptr, colidx, colidx_capacity, nnz   as in dr_build_mask; the kept blocks are a subset of the candidate
+ *                 blocks, so dr_mask_capacity bounds nnz here too
+ *   links         optional device uint8 [B, masks, N, N]: receives the link matrix (1 = kept); NULL: the context
+ *                 holds it in scratch of that size (DR_ERR_NOMEM if that allocation fails)
+ *   params->gamma, theta_c, theta_m, head_fuse (number of masks), has_tau_far, tau_far are read.
+ *   N <= 16384 and Hg * Wg <= 4096, else DR_ERR_UNSUPPORTED.  First use of a geometry synchronises once, like
+ *   dr_build_mask.
+ */
+dr_status dr_token_scores(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, int32_t head_fuse,
+                          float* scores, void* stream);
+dr_status dr_build_mask_tokens(dr_ctx* ctx, const dr_shape* shape, double tau_near, double lambda,
+                               const dr_mask_params* params, const float* token_scores, int32_t* rowptr,
+                               int32_t* colidx, int64_t colidx_capacity, int64_t* nnz, uint8_t* links, void* stream);
+
 /* Measurement aid (not a step of the method): average shader clock over a window.
  * Enqueues a one-wavefront kernel on `stream` that polls the constant 100 MHz counter for
  * `window_us` microseconds (1 .. 2 000 000) and then writes two uint64 to the device buffer

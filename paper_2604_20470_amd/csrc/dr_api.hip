@@ -31,6 +31,9 @@ struct dr_ctx {
     size_t uni_keep_bytes = 0, uni_count_bytes = 0;
     bool uni_valid = false;
     struct UniKey { double ratio, ratio_far; uint32_t seed; int32_t pad; } uni_key{};
+    // token-level order: link bytes [B, masks, N, N] when the caller does not ask for them
+    uint8_t* links = nullptr;
+    size_t links_bytes = 0;
     // cached candidate geometry
     uint8_t* class_map = nullptr;
     int32_t* row_sel = nullptr;
@@ -169,6 +172,18 @@ void fill_frame_table(int Nf, int Nt, int Bs, double gamma, double lambda, Frame
     }
 }
 
+Geometry make_geometry(const dr_shape* s, const dr_mask_params* p) {
+    Geometry g{};
+    const int Sb = (s->N + s->Bs - 1) / s->Bs;
+    g.N = s->N; g.Nt = s->Hg * s->Wg; g.Nf = s->Nf; g.Bs = s->Bs; g.Sb = Sb;
+    const int tail = s->N - (Sb - 1) * s->Bs;
+    g.row_min_full = min_count_exceeding(s->Bs, p->theta_c);
+    g.row_min_tail = min_count_exceeding(tail, p->theta_c);
+    g.col_min_full = min_count_exceeding(s->Bs, p->theta_m);
+    g.col_min_tail = min_count_exceeding(tail, p->theta_m);
+    return g;
+}
+
 dr_status ensure_geometry(dr_ctx* ctx, const dr_shape* s, double lambda, const dr_mask_params* p, hipStream_t stream) {
     const int Nt = s->Hg * s->Wg;
     dr_ctx::Key k{s->N, s->Nf, Nt, s->Bs, p->gamma, lambda, p->theta_c, p->theta_m};
@@ -180,13 +195,7 @@ dr_status ensure_geometry(dr_ctx* ctx, const dr_shape* s, double lambda, const d
     if ((st = grow(ctx, (void**)&ctx->class_map, &ctx->class_bytes, (size_t)Sb * Sb)) != DR_OK) return st;
     if ((st = grow(ctx, (void**)&ctx->row_sel, &ctx->rowsel_bytes, (size_t)Sb * 4)) != DR_OK) return st;
     if (!ctx->totals) DR_HIP(ctx, hipMalloc((void**)&ctx->totals, 2 * sizeof(unsigned long long)));
-    Geometry g{};
-    g.N = s->N; g.Nt = Nt; g.Nf = s->Nf; g.Bs = s->Bs; g.Sb = Sb;
-    const int tail = s->N - (Sb - 1) * s->Bs;
-    g.row_min_full = min_count_exceeding(s->Bs, p->theta_c);
-    g.row_min_tail = min_count_exceeding(tail, p->theta_c);
-    g.col_min_full = min_count_exceeding(s->Bs, p->theta_m);
-    g.col_min_tail = min_count_exceeding(tail, p->theta_m);
+    const Geometry g = make_geometry(s, p);
     FrameTab tab;
     fill_frame_table(s->Nf, Nt, s->Bs, p->gamma, lambda, &tab);
     DR_HIP(ctx, hipMemsetAsync(ctx->totals, 0, 2 * sizeof(unsigned long long), stream));
@@ -205,7 +214,7 @@ dr_status ensure_geometry(dr_ctx* ctx, const dr_shape* s, double lambda, const d
 
 extern "C" {
 
-const char* dr_version(void) { return "dynamicrad-gfx950 0.2"; }
+const char* dr_version(void) { return "dynamicrad-gfx950 0.3"; }
 
 dr_status dr_create(dr_ctx** out, int device) {
     if (!out) return DR_ERR_INVALID_ARG;
@@ -225,7 +234,7 @@ void dr_destroy(dr_ctx* ctx) {
     {
         DeviceGuard g(ctx->device);
         void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->row_sel, ctx->totals, ctx->gcol,
-                        ctx->gcount, ctx->uni_keep, ctx->uni_counts};
+                        ctx->gcount, ctx->uni_keep, ctx->uni_counts, ctx->links};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
     }
@@ -357,6 +366,66 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
         DR_HIP(ctx, launch_select_zscore(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
     else
         DR_HIP(ctx, launch_select(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
+    DR_HIP(ctx, launch_emit(ctx->keepbits, ctx->counts, shape->B, masks, Sb, false, rowptr, colidx, colidx_capacity, nnz, s));
+    return DR_OK;
+}
+
+dr_status dr_token_scores(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, int32_t head_fuse,
+                          float* scores, void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    dr_status st;
+    if ((st = check_tensor_shape(ctx, shape)) != DR_OK) return st;
+    if (!Q || !K || !scores) return fail(ctx, DR_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (head_fuse < 0 || head_fuse > shape->H) return fail(ctx, DR_ERR_INVALID_ARG, "head_fuse=%d outside 0..H", head_fuse);
+    if (shape->N > kMaxTokensTokenLevel)
+        return fail(ctx, DR_ERR_UNSUPPORTED, "N=%d exceeds %d for the token-level order", shape->N, kMaxTokensTokenLevel);
+    const int masks = head_fuse > 0 ? 1 : shape->H;
+    if ((int64_t)shape->B * masks > 65535) return fail(ctx, DR_ERR_UNSUPPORTED, "B * masks too large for the launch grid");
+    DeviceGuard g(ctx->device);
+    TensorDesc td{shape->stride_b, shape->stride_h, shape->stride_n, shape->B, shape->H, shape->N, shape->d};
+    DR_HIP(ctx, launch_token_scores(Q, K, shape->dtype == DR_BF16, td, masks, head_fuse > 0 ? head_fuse : 1, scores,
+                                    (hipStream_t)stream));
+    return DR_OK;
+}
+
+dr_status dr_build_mask_tokens(dr_ctx* ctx, const dr_shape* shape, double tau_near, double lambda,
+                               const dr_mask_params* params, const float* token_scores, int32_t* rowptr,
+                               int32_t* colidx, int64_t colidx_capacity, int64_t* nnz, uint8_t* links, void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    const dr_mask_params* p = params ? params : &kDefaults;
+    dr_status st;
+    if ((st = check_geometry(ctx, shape)) != DR_OK) return st;
+    if ((st = check_params(ctx, p, lambda)) != DR_OK) return st;
+    if (shape->B <= 0 || shape->H <= 0) return fail(ctx, DR_ERR_INVALID_ARG, "non-positive B or H");
+    if (shape->B > 65535 || shape->H > 65535) return fail(ctx, DR_ERR_UNSUPPORTED, "B or H too large for the launch grid");
+    if (std::isnan(tau_near)) return fail(ctx, DR_ERR_INVALID_ARG, "tau_1 is NaN");
+    if (p->head_fuse > shape->H) return fail(ctx, DR_ERR_INVALID_ARG, "head_fuse=%d > H", p->head_fuse);
+    if (!token_scores || !rowptr || !colidx || !nnz) return fail(ctx, DR_ERR_INVALID_ARG, "NULL output or scores pointer");
+    if (colidx_capacity <= 0) return fail(ctx, DR_ERR_CAPACITY, "colidx_capacity must be > 0");
+    const int Nt = shape->Hg * shape->Wg;
+    if (shape->N > kMaxTokensTokenLevel || Nt > kMaxFrameTokensTokenLevel)
+        return fail(ctx, DR_ERR_UNSUPPORTED, "N=%d / Nt=%d exceed %d / %d for the token-level order", shape->N, Nt,
+                    kMaxTokensTokenLevel, kMaxFrameTokensTokenLevel);
+    DeviceGuard g(ctx->device);
+    hipStream_t s = (hipStream_t)stream;
+    if ((st = ensure_geometry(ctx, shape, lambda, p, s)) != DR_OK) return st;
+    const int Sb = (shape->N + shape->Bs - 1) / shape->Bs;
+    const int masks = p->head_fuse > 0 ? 1 : shape->H;
+    const size_t rows = (size_t)shape->B * masks * Sb;
+    const size_t words = (Sb + 31) / 32;
+    if ((st = grow(ctx, (void**)&ctx->keepbits, &ctx->keep_bytes, rows * words * 4)) != DR_OK) return st;
+    if ((st = grow(ctx, (void**)&ctx->counts, &ctx->count_bytes, rows * 4)) != DR_OK) return st;
+    if (!links) {
+        const size_t need = (size_t)shape->B * masks * (size_t)shape->N * (size_t)shape->N;
+        if ((st = grow(ctx, (void**)&ctx->links, &ctx->links_bytes, need)) != DR_OK) return st;
+        links = ctx->links;
+    }
+    FrameTab tab;
+    fill_frame_table(shape->Nf, Nt, shape->Bs, p->gamma, lambda, &tab);
+    const Geometry geo = make_geometry(shape, p);
+    DR_HIP(ctx, launch_pair_links(token_scores, tab, shape->B, masks, shape->N, Nt, shape->Nf, tau_near,
+                                  p->has_tau_far ? p->tau_far : tau_near, links, s));
+    DR_HIP(ctx, launch_aggregate_links(links, ctx->class_map, geo, shape->B, masks, ctx->keepbits, ctx->counts, s));
     DR_HIP(ctx, launch_emit(ctx->keepbits, ctx->counts, shape->B, masks, Sb, false, rowptr, colidx, colidx_capacity, nnz, s));
     return DR_OK;
 }

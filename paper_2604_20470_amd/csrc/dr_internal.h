@@ -9,6 +9,8 @@ namespace dr {
 
 constexpr int kMaxFrames = 256;          // per-t table travels as a kernel argument
 constexpr int kMaxSelectablePerRow = 8192;
+constexpr int kMaxTokensTokenLevel = 16384;   // the token-level order holds [N, N] matrices
+constexpr int kMaxFrameTokensTokenLevel = 4096;
 
 // Per temporal distance t (paper Eqs. 1-6, evaluated on the host in fp64).
 struct FrameTab {
@@ -57,6 +59,17 @@ hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, i
                                 const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
 hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb, bool shared,
                        int32_t* rowptr, int32_t* colidx, int64_t capacity, int64_t* nnz, hipStream_t s);
+
+// ---- Algorithm 1 in its own order (token-pair selection, then aggregation), small N -----------------
+// scores[b][m][p][q] = (1 / (heads_per_mask * sqrt(d))) * sum_h Q_p . K_q
+hipError_t launch_token_scores(const void* Q, const void* K, bool bf16, const TensorDesc& td, int masks,
+                               int heads_per_mask, float* scores, hipStream_t s);
+// links[b][m][p][q] = 1 where the token pair is kept (z-score thresholds inside every frame pair's candidate set)
+hipError_t launch_pair_links(const float* scores, const FrameTab& tab, int B, int masks, int N, int Nt, int Nf,
+                             double tau_near, double tau_far, uint8_t* links, hipStream_t s);
+// density rule per block pair -> the keepbits / counts that launch_emit reads
+hipError_t launch_aggregate_links(const uint8_t* links, const uint8_t* class_map, const Geometry& g, int B, int masks,
+                                  uint32_t* keepbits, int32_t* counts, hipStream_t s);
 
 // ---- stage (c) -------------------------------------------------------------------------
 struct AttnArgs {

@@ -1,0 +1,141 @@
+"""GPU parity for Algorithm 1 in the paper's own order (token scores, z-score links per frame pair, aggregation to
+blocks).  Token scores are compared within the block-score tolerance; links and masks bit for bit, with the oracle
+selecting from the GPU's own fp32 token scores."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_20470_amd as dr
+from oracle import dynamicrad_oracle as o
+from workloads import Workload, tiny_case
+
+from helpers import GpuRun, assert_masks_equal, oracle_class_map, score_error
+
+pytestmark = pytest.mark.gpu
+
+MID = Workload("mid2k", 31, 1, 2, 128, 8, 16, 16, 32, "bf16", "field", "dynamic", 0.5, 0.9, 1.0)
+CASES = [tiny_case("tiny8"), tiny_case("ragged"), tiny_case("ragged128"), MID]
+SCORE_TOL = 1e-5
+
+
+def _ids(w):
+    return f"{w.name}-Bs{w.Bs}"
+
+
+def _token_scores(run, head_fuse):
+    wl = run.wl
+    masks = 1 if head_fuse > 0 else len(run.heads)
+    s = torch.full((wl.B, masks, wl.N, wl.N), float("nan"), dtype=torch.float32, device=run.device)
+    dr.dr_token_scores(run.ctx, run.shape, run.Q, run.K, head_fuse, s)
+    torch.cuda.synchronize()
+    return s
+
+
+def _build(run, scores, tau, lam=None, want_links=True):
+    wl = run.wl
+    lam = wl.lam if lam is None else lam
+    cap, _ = dr.dr_mask_capacity(run.ctx, run.shape, lam, run.params)
+    B, M = scores.shape[:2]
+    rowptr = torch.full((B, M, run.Sb + 1), -7, dtype=torch.int32, device=run.device)
+    colidx = torch.full((B * M * cap + 64,), -7, dtype=torch.int32, device=run.device)
+    nnz = torch.full((B, M), -7, dtype=torch.int64, device=run.device)
+    links = torch.full((B, M, wl.N, wl.N), 9, dtype=torch.uint8, device=run.device) if want_links else None
+    dr.dr_build_mask_tokens(run.ctx, run.shape, tau, lam, run.params, scores, rowptr, colidx, cap, nnz, links)
+    torch.cuda.synchronize()
+    assert (colidx[B * M * cap:] == -7).all(), "colidx guard overwritten"
+    return rowptr, colidx[:B * M * cap].view(B, M, cap), nnz, cap, links
+
+
+@pytest.mark.parametrize("wl", CASES, ids=_ids)
+@pytest.mark.parametrize("head_fuse", [2, 0])
+def test_token_scores_match_the_oracle(wl, head_fuse):
+    run = GpuRun(wl)
+    got = _token_scores(run, head_fuse)
+    want = o.token_scores(run.Qc.double().numpy(), run.Kc.double().numpy(), head_fuse)
+    err = score_error(got, want)
+    print(f"{wl.name} head_fuse={head_fuse}: token-score error {err:.2e}")
+    assert err <= SCORE_TOL
+
+
+@pytest.mark.parametrize("wl", CASES, ids=_ids)
+def test_links_and_masks_bit_exact(wl):
+    for gamma, head_fuse in ((1.0, 2), (3.0, 0)):
+        for tau1, tau2 in ((0.0, None), (0.8, -0.4), (-1.0, 1.5), (float("-inf"), float("-inf")), (40.0, 40.0)):
+            run = GpuRun(wl, params=dr.MaskParams(gamma=gamma, head_fuse=head_fuse, tau_far=tau2))
+            scores = _token_scores(run, head_fuse)
+            rowptr, colidx, nnz, cap, links = _build(run, scores, tau1)
+            tab = o.frame_table(wl.Nf, wl.Nt, wl.Bs, gamma, wl.lam)
+            sc = scores.cpu().numpy()
+            for b in range(sc.shape[0]):
+                for m in range(sc.shape[1]):
+                    want_links = o.select_token_links(sc[b, m], wl.N, wl.Nt, tab, tau1, tau1 if tau2 is None else tau2)
+                    got_links = links[b, m].cpu().numpy()
+                    assert set(np.unique(got_links)) <= {0, 1}
+                    assert (got_links.astype(bool) == want_links).all(), (wl.name, gamma, tau1, tau2, b, m)
+            want = o.build_mask_from_tokens(sc, wl.N, wl.Nt, wl.Bs, tab, 0.15, 0.60, tau1, tau2)
+            assert_masks_equal(rowptr, colidx, nnz, want)
+            if tau1 == float("-inf"):          # everything passes: the candidate geometry itself
+                cls = run.class_map().cpu().numpy()
+                assert int(nnz[0, 0]) == int((cls != 0).sum())
+            # the context's own link scratch gives the same mask
+            rowptr2, colidx2, nnz2, _, _ = _build(run, scores, tau1, want_links=False)
+            assert torch.equal(rowptr, rowptr2) and torch.equal(nnz, nnz2) and torch.equal(colidx, colidx2)
+
+
+def test_density_thresholds_and_lambda_are_followed():
+    wl = tiny_case("ragged")
+    for theta_c, theta_m, lam in ((0.5, 0.3, 1.0), (0.05, 0.9, 0.4), (0.15, 0.6, 2.0)):
+        run = GpuRun(wl, params=dr.MaskParams(gamma=3.0, theta_c=theta_c, theta_m=theta_m, head_fuse=2))
+        scores = _token_scores(run, 2)
+        rowptr, colidx, nnz, cap, _ = _build(run, scores, 0.3, lam=lam)
+        tab = o.frame_table(wl.Nf, wl.Nt, wl.Bs, 3.0, lam)
+        want = o.build_mask_from_tokens(scores.cpu().numpy(), wl.N, wl.Nt, wl.Bs, tab, theta_c, theta_m, 0.3)
+        assert_masks_equal(rowptr, colidx, nnz, want)
+
+
+def test_constant_scores_and_fallback():
+    """sigma = 0: z = 0, so tau <= 0 keeps every candidate pair and tau > 0 only the first pair of each set."""
+    wl = tiny_case("tiny8")
+    run = GpuRun(wl, params=dr.MaskParams(gamma=3.0))
+    tab = o.frame_table(wl.Nf, wl.Nt, wl.Bs, 3.0, wl.lam)
+    scores = torch.full((wl.B, 1, wl.N, wl.N), 0.375, dtype=torch.float32, device="cuda")
+    _, _, _, _, links = _build(run, scores, 0.0)
+    assert (links[0, 0].cpu().numpy().astype(bool) == o.candidate_matrix(wl.N, wl.Nt, tab)).all()
+    rowptr, colidx, nnz, cap, links = _build(run, scores, 0.5)
+    want = o.select_token_links(scores[0, 0].cpu().numpy(), wl.N, wl.Nt, tab, 0.5, 0.5)
+    assert (links[0, 0].cpu().numpy().astype(bool) == want).all()
+    cls = oracle_class_map(wl, gamma=3.0)
+    assert int(nnz[0, 0]) == int((cls == 3).sum())
+
+
+def test_token_level_mask_feeds_the_attention_stage():
+    wl = MID
+    run = GpuRun(wl, params=dr.MaskParams(head_fuse=2))
+    scores = _token_scores(run, 2)
+    rowptr, colidx, nnz, cap, _ = _build(run, scores, 0.5, want_links=False)
+    assert 0 < int(nnz[0, 0]) < wl.Sb * wl.Sb
+    O = run.attention(rowptr, colidx, cap)
+    rp = rowptr[0, 0].cpu().numpy().astype(np.int64)
+    ci = colidx[0, 0, :rp[-1]].cpu().numpy().astype(np.int64)
+    for h in range(len(run.heads)):
+        rows = [0, 7, wl.Sb // 2, wl.Sb - 1]
+        want = o.masked_attention(run.Qc[0, h].double().numpy(), run.Kc[0, h].double().numpy(),
+                                  run.Vc[0, h].double().numpy(), rp, ci, wl.Bs, rows=rows)
+        got = O[0, h].float().cpu().numpy()
+        for qb in rows:
+            assert np.abs(got[qb * wl.Bs:(qb + 1) * wl.Bs] - want[qb]).max() <= 2e-2
+
+
+def test_limits_and_argument_errors():
+    wl = tiny_case("tiny8")
+    run = GpuRun(wl)
+    scores = _token_scores(run, 2)
+    with pytest.raises(dr.DRError):
+        _build(run, scores, float("nan"))
+    big = dr.Shape.from_buffer_copy(run.shape)
+    big.N, big.Nf = 8 * 64 * 40, 8 * 40                     # 20480 tokens: past the limit of the token-level order
+    dummy = torch.zeros(16, dtype=torch.float32, device="cuda")
+    with pytest.raises(dr.DRError):
+        dr.dr_token_scores(run.ctx, big, run.Q, run.K, 2, dummy)
+    with pytest.raises(dr.DRError):
+        dr.dr_build_mask_tokens(run.ctx, big, 0.0, 1.0, None, dummy, dummy, dummy, 16, dummy, None)
