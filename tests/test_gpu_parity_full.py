@@ -104,7 +104,7 @@ def test_paper_selection_rules_full(name, heads):
     print(f"[{name}] uniform nnz={int(nnz[0, 0])} sparsity={1 - int(nnz[0, 0]) / wl.Sb ** 2:.4f}", flush=True)
 
 
-@pytest.mark.parametrize("name,bs", [("cfg3", 64), ("cfg3", 32), ("cfg4", 64)])
+@pytest.mark.parametrize("name,bs", [("cfg3", 64), ("cfg3", 32), ("cfg4", 64), ("cfg4", 32), ("micro264k", 32)])
 def test_small_block_sizes_full(name, bs):
     """The benchmark geometries at Bs = 64 / 32 (MFMA path that walks the union of several CSR rows): scores, masks in
     full, attention on sampled query blocks."""
