@@ -4,7 +4,8 @@
 // k_pool is the HBM-bound part: each workgroup streams one block of Bs token rows
 // with 16-byte loads (a wavefront covers whole 256/512-byte rows, so every request
 // is fully coalesced), accumulates in fp32 registers and folds the per-thread
-// partials through LDS.  k_scores is a small fp32 GEMM over the pooled vectors.
+// partials through LDS.  k_scores_mfma is an fp32 GEMM over the pooled vectors on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32: fp32 products and accumulation, as the 1e-5 score tolerance asks).
 #include "dr_internal.h"
 
 #include <hip/hip_bf16.h>
@@ -86,61 +87,98 @@ __global__ __launch_bounds__(kPoolThreads) void k_pool(const void* __restrict__ 
     }
 }
 
-// scores tile: 64 x 64 outputs per workgroup, 4 x 4 per thread, contraction chunks of 32 through LDS.
-constexpr int kTile = 64, kChunk = 32;
+typedef float v16f __attribute__((ext_vector_type(16)));
 
-// grid: (ceil(Sb/64), ceil(Sb/64), B*masks)
-__global__ __launch_bounds__(256) void k_scores(const float* __restrict__ pooled, int B, int Hs, int masks,
-                                                int heads_per_mask, int Sb, int d, float scale,
-                                                float* __restrict__ scores) {
-    __shared__ float As[kChunk][kTile + 4];
-    __shared__ float Bt[kChunk][kTile + 4];
+// scores on the fp32 matrix cores: a workgroup of 2 x 2 waves, each wave WT x WT tiles of v_mfma_f32_32x32x2_f32,
+// contraction chunks of 32 staged through LDS.  The instruction contracts two k per issue (lane halves); a lane
+// reads four consecutive k of its row with one 16-byte LDS load (k = 4 * half + c within a group of eight) and feeds
+// component c to issue c: the k order inside a group is permuted identically for both operands, which a sum does
+// not mind.  WT = 2 (128 x 128 outputs per workgroup) once there are enough tiles to fill the chip, WT = 1 below.
+constexpr int kMChunk = 32, kMPad = 36;      // row pitch 144 B keeps the 16-byte reads of 32 rows off the same banks
+
+template <int WT>
+__global__ __launch_bounds__(256) void k_scores_mfma(const float* __restrict__ pooled, int B, int Hs, int masks,
+                                                     int heads_per_mask, int Sb, int d, float scale,
+                                                     float* __restrict__ scores) {
+    constexpr int TILE = 64 * WT;
+    __shared__ __attribute__((aligned(16))) float As[TILE][kMPad];
+    __shared__ __attribute__((aligned(16))) float Bs[TILE][kMPad];
     const int bm = blockIdx.z, b = bm / masks, m = bm % masks;
-    const int q0 = blockIdx.y * kTile, k0 = blockIdx.x * kTile;
-    const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+    const int q0 = blockIdx.y * TILE, k0 = blockIdx.x * TILE;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wr = (wave >> 1) * 32 * WT, wc = (wave & 1) * 32 * WT;     // this wave's corner inside the tile
     const int h0 = (masks == 1) ? 0 : m;
-    float acc[4][4] = {};
+    v16f acc[WT][WT];
+#pragma unroll
+    for (int i = 0; i < WT; ++i)
+#pragma unroll
+        for (int j = 0; j < WT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     const int64_t plane = (int64_t)Sb * d;
-    for (int hh = 0; hh < heads_per_mask; ++hh) {
+    constexpr int NV = TILE * 8 / 256;             // float4 per thread and operand in one chunk (TILE rows x 32 floats)
+    float4 pa[NV], pb[NV];
+    const int chunks_per_head = d / kMChunk, steps = heads_per_mask * chunks_per_head;
+    auto fetch = [&](int step) {                   // the next chunk travels in registers while this one is multiplied
+        const int hh = step / chunks_per_head, c0 = (step % chunks_per_head) * kMChunk;
         const float* qb = pooled + ((int64_t)b * Hs + h0 + hh) * plane;
         const float* kb = pooled + (((int64_t)B + b) * Hs + h0 + hh) * plane;
-        for (int c0 = 0; c0 < d; c0 += kChunk) {
-            // 64 rows x 32 floats = 512 float4 per operand; two per thread
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int idx = tid + it * 256;
-                const int row = idx / 8, c4 = (idx % 8) * 4;
-                float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
-                if (q0 + row < Sb) va = *reinterpret_cast<const float4*>(qb + (int64_t)(q0 + row) * d + c0 + c4);
-                if (k0 + row < Sb) vb = *reinterpret_cast<const float4*>(kb + (int64_t)(k0 + row) * d + c0 + c4);
-                As[c4 + 0][row] = va.x; As[c4 + 1][row] = va.y; As[c4 + 2][row] = va.z; As[c4 + 3][row] = va.w;
-                Bt[c4 + 0][row] = vb.x; Bt[c4 + 1][row] = vb.y; Bt[c4 + 2][row] = vb.z; Bt[c4 + 3][row] = vb.w;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int c = 0; c < kChunk; ++c) {
-                const float4 a = *reinterpret_cast<const float4*>(&As[c][ty * 4]);
-                const float4 bb = *reinterpret_cast<const float4*>(&Bt[c][tx * 4]);
-                const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {bb.x, bb.y, bb.z, bb.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
-            }
-            __syncthreads();
+        for (int it = 0; it < NV; ++it) {
+            const int idx = tid + it * 256;
+            const int row = idx >> 3, c4 = (idx & 7) * 4;
+            pa[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            pb[it] = pa[it];
+            if (q0 + row < Sb) pa[it] = *reinterpret_cast<const float4*>(qb + (int64_t)(q0 + row) * d + c0 + c4);
+            if (k0 + row < Sb) pb[it] = *reinterpret_cast<const float4*>(kb + (int64_t)(k0 + row) * d + c0 + c4);
         }
+    };
+    fetch(0);
+    for (int step = 0; step < steps; ++step) {
+#pragma unroll
+        for (int it = 0; it < NV; ++it) {
+            const int idx = tid + it * 256;
+            const int row = idx >> 3, c4 = (idx & 7) * 4;
+            *reinterpret_cast<float4*>(&As[row][c4]) = pa[it];
+            *reinterpret_cast<float4*>(&Bs[row][c4]) = pb[it];
+        }
+        __syncthreads();
+        if (step + 1 < steps) fetch(step + 1);
+#pragma unroll
+        for (int g8 = 0; g8 < kMChunk; g8 += 8) {
+            float4 a[WT], bb[WT];
+#pragma unroll
+            for (int i = 0; i < WT; ++i) {
+                a[i] = *reinterpret_cast<const float4*>(&As[wr + i * 32 + l32][g8 + 4 * half]);
+                bb[i] = *reinterpret_cast<const float4*>(&Bs[wc + i * 32 + l32][g8 + 4 * half]);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int i = 0; i < WT; ++i)
+#pragma unroll
+                    for (int j = 0; j < WT; ++j) {
+                        const float av = c == 0 ? a[i].x : c == 1 ? a[i].y : c == 2 ? a[i].z : a[i].w;
+                        const float bv = c == 0 ? bb[j].x : c == 1 ? bb[j].y : c == 2 ? bb[j].z : bb[j].w;
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                    }
+        }
+        __syncthreads();
     }
+    // accumulator element e of lane (l32, half): row 8 * (e / 4) + 4 * half + e % 4, column l32
     float* out = scores + (int64_t)bm * Sb * Sb;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int qr = q0 + ty * 4 + i;
-        if (qr >= Sb) continue;
+    for (int i = 0; i < WT; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int kc = k0 + tx * 4 + j;
-            if (kc < Sb) out[(int64_t)qr * Sb + kc] = acc[i][j] * scale;
+        for (int j = 0; j < WT; ++j) {
+            const int kc = k0 + wc + j * 32 + l32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int qr = q0 + wr + i * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                if (qr < Sb && kc < Sb) out[(int64_t)qr * Sb + kc] = acc[i][j][e] * scale;
+            }
         }
-    }
 }
 
 }  // namespace
@@ -160,10 +198,14 @@ hipError_t launch_pool(const void* Q, const void* K, bool bf16, const TensorDesc
 
 hipError_t launch_scores(const float* pooled, int B, int Hs, int masks, int heads_per_mask, int Sb, int d,
                          float* scores, hipStream_t s) {
-    const int t = (Sb + kTile - 1) / kTile;
     const float scale = 1.0f / (sqrtf((float)d) * (float)heads_per_mask);
-    hipLaunchKernelGGL(k_scores, dim3(t, t, B * masks), dim3(256), 0, s, pooled, B, Hs, masks, heads_per_mask, Sb, d,
-                       scale, scores);
+    const int t128 = (Sb + 127) / 128, t64 = (Sb + 63) / 64;
+    if ((int64_t)t128 * t128 * B * masks >= 512)
+        hipLaunchKernelGGL(k_scores_mfma<2>, dim3(t128, t128, B * masks), dim3(256), 0, s, pooled, B, Hs, masks,
+                           heads_per_mask, Sb, d, scale, scores);
+    else
+        hipLaunchKernelGGL(k_scores_mfma<1>, dim3(t64, t64, B * masks), dim3(256), 0, s, pooled, B, Hs, masks,
+                           heads_per_mask, Sb, d, scale, scores);
     return hipGetLastError();
 }
 
