@@ -362,6 +362,12 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
         DR_HIP(ctx, launch_emit(ctx->uni_keep, ctx->uni_counts, shape->B, masks, Sb, true, rowptr, colidx, colidx_capacity, nnz, s));
         return DR_OK;
     }
+    if (mode == DR_MODE_ZSCORE_THRESHOLD) {
+        FrameTab tab;
+        fill_frame_table(shape->Nf, a.Nt, shape->Bs, p->gamma, lambda, &tab);
+        for (int t = 0; t < shape->Nf; ++t)
+            if (((tab.flags[t] >> 1) & 3) == DR_CLASS_NEAR) a.near_mask[t >> 6] |= 1ull << (t & 63);
+    }
     if (mode == DR_MODE_ZSCORE_THRESHOLD)
         DR_HIP(ctx, launch_select_zscore(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
     else

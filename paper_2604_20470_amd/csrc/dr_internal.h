@@ -50,6 +50,7 @@ struct SelectArgs {
     int32_t sort_cap;        // power of two >= the largest selectable count of a row
     uint32_t seed;           // uniform mode
     int32_t N, Nt, Nf, Bs;   // geometry, for the candidate sets of the z-score mode
+    uint64_t near_mask[kMaxFrames / 64];   // z-score mode: bit t set when the decay length at frame distance t is >= Bs
 };
 // keepbits[(b*masks+m)*Sb + qb][words], counts[(b*masks+m)*Sb + qb]
 hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,

@@ -9,7 +9,7 @@
 //                keep-one fallback of Eq. 11 / Algorithm 1).
 //                In the seeded uniform mode (Eq. 8 as worded in the paper) the sort key is a
 //                counter-based hash of (seed, query block, key block) instead of the score.
-//   k_select_zscore  the paper's dynamic rule (Eqs. 10-11) per row: lanes own candidate sets
+//   k_select_zscore  the paper's dynamic rule (Eqs. 10-11), one wavefront per row: lanes own candidate sets
 //                (frame distance, side), standardise the scores of a set in fp64 and keep
 //                z >= tau_1 / tau_2, with the keep-one fallback.
 //   k_emit       per row: offset = sum of the previous rows' counts, bit-expansion to
@@ -208,7 +208,17 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
             __syncthreads();
             if (tid == 0) {          // one-by-one summation in the total order: the order is part of the definition
                 double cum = 0.0;
-                for (int i = 0; i < n; ++i) { cum = cum + mass[i]; mass[i] = cum; }
+                int i = 0;
+                for (; i + 8 <= n; i += 8) {          // eight loads in flight, then the dependent chain of additions
+                    double v[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = mass[i + e];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) { cum = cum + v[e]; v[e] = cum; }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) mass[i + e] = v[e];
+                }
+                for (; i < n; ++i) { cum = cum + mass[i]; mass[i] = cum; }
             }
             __syncthreads();
             const double target = a.tau * mass[n - 1];
@@ -226,67 +236,116 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
     store_row(keep, words, row, keepbits, counts, &s_cnt);
 }
 
-// grid: (Sb, masks, B).  LDS: keep[words] u32.  Thread g owns the candidate sets g, g + 256, ...; set id =
-// 2 * (frame gap) + (key block after the query block).  The three passes over a set run in ascending key-block
-// order, one addition at a time, with floating-point contraction off: the summation order and the absence of fused
-// multiply-adds are part of the definition the results are compared against.
+// grid: (Sb, masks, B).  A candidate set of the row is identified by the frame f that realises its gap: the key
+// blocks whose first frame is f (f after the query block) or whose last frame is f (f before it); they lie in the
+// key-block range of frame f, at most `maxlen` blocks.
+// TILED (LDS: keep[words] u32 | tile[maxlen][Nf] f32): all threads first scatter the row's selectable scores into
+// the tile, position inside the set's range major, frame minor (reads of the row coalesced, the frame arithmetic once
+// per key block); a lane then walks "its" frame's column: neighbouring lanes read neighbouring LDS words, and nothing
+// in the serial part touches global memory.  Cells that hold no member keep a sentinel (a NaN pattern; scores are
+// finite).  Without TILED (tile too large for LDS) a lane reads its range from global memory.
+// The three passes over a set run in ascending key-block order, one addition at a time, with floating-point
+// contraction off: the summation order and the absence of fused multiply-adds are part of the definition the
+// results are compared against.  A cell outside the set adds +0.0, which leaves the running sums bit for bit as they
+// are (they start at +0.0 and so are never -0.0), so the loops carry no branch.
+// The threshold test is the quotient (s - mu) / (sigma + eps) >= tau in IEEE double.  A division costs about ten
+// double-precision instructions, so the quotient is first estimated with a reciprocal (relative error <= 2^-52);
+// only when the estimate lies within 2^-50 |tau| of tau is the division itself evaluated.
+constexpr uint32_t kNoMember = 0x7fc0dead;
+
+template <bool TILED>
 __global__ __launch_bounds__(kThreads) void k_select_zscore(const uint8_t* __restrict__ class_map,
                                                             const float* __restrict__ scores, int masks, int Sb,
-                                                            SelectArgs a, uint32_t* __restrict__ keepbits,
+                                                            int maxlen, SelectArgs a, uint32_t* __restrict__ keepbits,
                                                             int32_t* __restrict__ counts) {
 #pragma clang fp contract(off)
     extern __shared__ unsigned char smem[];
+    const int words = (Sb + 31) / 32;
     uint32_t* keep = reinterpret_cast<uint32_t*>(smem);
+    uint32_t* tile = reinterpret_cast<uint32_t*>(smem + (size_t)words * 4);     // [maxlen][Nf], score bits
     __shared__ int s_cnt;
     const int qb = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x;
-    const int words = (Sb + 31) / 32;
     const int64_t row = ((int64_t)b * masks + m) * Sb + qb;
     const float* srow = scores + row * Sb;
     const uint8_t* crow = class_map + (int64_t)qb * Sb;
     for (int i = tid; i < words; i += kThreads) keep[i] = 0u;
     if (tid == 0) s_cnt = 0;
+    if (TILED)
+        for (int i = tid; i < maxlen * a.Nf; i += kThreads) tile[i] = kNoMember;
     __syncthreads();
-    for (int kb = tid; kb < Sb; kb += kThreads)
-        if (crow[kb] == 3) atomicOr(&keep[kb >> 5], 1u << (kb & 31));
     const int r0 = qb * a.Bs, r1 = min(a.N, r0 + a.Bs);
     const int i0 = r0 / a.Nt, i1 = (r1 - 1) / a.Nt;
-    for (int gid = 4 + tid; gid < 2 * a.Nf; gid += kThreads) {       // gaps 0 and 1 are the never-pruned zone
-        const int gap = gid >> 1;
-        const bool after = gid & 1;
-        const int f = after ? i1 + gap : i0 - gap;                   // the frame that realises the gap
-        if (f < 0 || f >= a.Nf) continue;
-        const int kb_lo = (int)(((int64_t)f * a.Nt) / a.Bs);
-        const int kb_hi = min(Sb - 1, (int)((((int64_t)f + 1) * a.Nt - 1) / a.Bs));
-        auto member = [&](int kb) {
-            const int c = crow[kb];
-            if (c != 1 && c != 2) return false;
-            const int c0 = kb * a.Bs, c1 = min(a.N, c0 + a.Bs);
-            const int j0 = c0 / a.Nt, j1 = (c1 - 1) / a.Nt;
-            return after ? (j0 - i1 == gap) : (i0 - j1 == gap);
+    for (int kb = tid; kb < Sb; kb += kThreads) {
+        const int c = crow[kb];
+        if (c == 3) atomicOr(&keep[kb >> 5], 1u << (kb & 31));
+        if (TILED && (c == 1 || c == 2)) {
+            const uint32_t c0 = (uint32_t)kb * (uint32_t)a.Bs;                   // < N <= 2^31 - 1: 32-bit divisions
+            const int j0 = (int)(c0 / (uint32_t)a.Nt);
+            const int j1 = (int)((min((uint32_t)a.N, c0 + (uint32_t)a.Bs) - 1u) / (uint32_t)a.Nt);
+            const int f = j0 > i1 ? j0 : j1;                                     // selectable: j0 > i1 + 1 or j1 < i0 - 1
+            const int pos = kb - (int)(((uint32_t)f * (uint32_t)a.Nt) / (uint32_t)a.Bs);
+            tile[pos * a.Nf + f] = __float_as_uint(srow[kb]);
+        }
+    }
+    if (TILED) __syncthreads();
+    for (int f = tid; f < a.Nf; f += kThreads) {
+        const bool after = f > i1 + 1, before = f < i0 - 1;                      // gaps 0 and 1 are the never-pruned zone
+        if (!after && !before) continue;
+        const int gap = after ? f - i1 : i0 - f;
+        const int64_t f_lo = (int64_t)f * a.Nt, f_hi = f_lo + a.Nt;              // tokens of frame f
+        const int kb_lo = (int)(f_lo / a.Bs);
+        const int len = min(Sb - 1, (int)((f_hi - 1) / a.Bs)) - kb_lo + 1;
+        // cell p of the set: score bits, or kNoMember
+        auto cell = [&](int p) -> uint32_t {
+            if (TILED) return tile[p * a.Nf + f];
+            const int kb = kb_lo + p, c = crow[kb];
+            const int64_t c0 = (int64_t)kb * a.Bs;
+            const int64_t edge = after ? c0 : min((int64_t)a.N, c0 + a.Bs) - 1;
+            return ((c == 1 || c == 2) && edge >= f_lo && edge < f_hi) ? __float_as_uint(srow[kb]) : kNoMember;
         };
         int n = 0;
         double sum = 0.0;
-        for (int kb = kb_lo; kb <= kb_hi; ++kb)
-            if (member(kb)) { sum = sum + (double)srow[kb]; ++n; }
+#pragma unroll 4
+        for (int p = 0; p < len; ++p) {
+            const uint32_t v = cell(p);
+            const bool in = v != kNoMember;
+            sum = sum + (in ? (double)__uint_as_float(v) : 0.0);
+            n += in ? 1 : 0;
+        }
         if (n == 0) continue;
         const double mu = sum / (double)n;
         double ssq = 0.0;
-        for (int kb = kb_lo; kb <= kb_hi; ++kb)
-            if (member(kb)) { const double dlt = (double)srow[kb] - mu; const double sq = dlt * dlt; ssq = ssq + sq; }
+#pragma unroll 4
+        for (int p = 0; p < len; ++p) {
+            const uint32_t v = cell(p);
+            const double dlt = (double)__uint_as_float(v) - mu;
+            const double sq = dlt * dlt;
+            ssq = ssq + (v != kNoMember ? sq : 0.0);
+        }
         const double denom = sqrt(ssq / (double)n) + 1e-6;
+        const double rcp = 1.0 / denom;
+        // every member of the set has the same smallest frame distance (the gap), hence the same decay state
+        const double tau = ((a.near_mask[gap >> 6] >> (gap & 63)) & 1ull) ? a.tau_near : a.tau_far;
+        // estimates outside [tau_lo, tau_hi] decide by themselves; an infinite tau never needs the division
+        const double slack = fabs(tau) != INFINITY ? 8.9e-16 * fabs(tau) + 1e-290 : 0.0;
+        const double tau_lo = tau - slack, tau_hi = tau + slack;
         bool any = false;
-        int best_kb = -1;
+        int best_p = -1;
         float best_s = 0.f;
-        for (int kb = kb_lo; kb <= kb_hi; ++kb)
-            if (member(kb)) {
-                const float x = srow[kb];
-                const double z = ((double)x - mu) / denom;
-                const double tau = (crow[kb] == 1) ? a.tau_near : a.tau_far;
-                if (z >= tau) { any = true; atomicOr(&keep[kb >> 5], 1u << (kb & 31)); }
-                if (best_kb < 0 || x > best_s) { best_kb = kb; best_s = x; }
-            }
-        if (!any) atomicOr(&keep[best_kb >> 5], 1u << (best_kb & 31));
+#pragma unroll 4
+        for (int p = 0; p < len; ++p) {
+            const uint32_t v = cell(p);
+            if (v == kNoMember) continue;
+            const float x = __uint_as_float(v);
+            const double dev = (double)x - mu;
+            const double est = dev * rcp;
+            bool pass = est >= tau;
+            if (est >= tau_lo && est <= tau_hi && slack != 0.0) pass = dev / denom >= tau;
+            if (pass) { any = true; atomicOr(&keep[(kb_lo + p) >> 5], 1u << ((kb_lo + p) & 31)); }
+            if (best_p < 0 || x > best_s) { best_p = p; best_s = x; }
+        }
+        if (!any) atomicOr(&keep[(kb_lo + best_p) >> 5], 1u << ((kb_lo + best_p) & 31));
     }
     __syncthreads();
     store_row(keep, words, row, keepbits, counts, &s_cnt);
@@ -377,9 +436,21 @@ hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, i
 
 hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
                                 const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s) {
-    const size_t lds = (size_t)((Sb + 31) / 32) * 4;
-    hipLaunchKernelGGL(k_select_zscore, dim3(Sb, masks, B), dim3(kThreads), lds, s, class_map, scores, masks, Sb, a,
-                       keepbits, counts);
+    const size_t words = (Sb + 31) / 32;
+    const int maxlen = (a.Nt + a.Bs - 1) / a.Bs + 1;          // key blocks that can touch one frame
+    const size_t tiled = words * 4 + (size_t)maxlen * a.Nf * 4;
+    if (tiled <= 144 * 1024) {
+        if (tiled > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_zscore<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiled);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(k_select_zscore<true>, dim3(Sb, masks, B), dim3(kThreads), tiled, s, class_map, scores, masks,
+                           Sb, maxlen, a, keepbits, counts);
+    } else {
+        hipLaunchKernelGGL(k_select_zscore<false>, dim3(Sb, masks, B), dim3(kThreads), words * 4, s, class_map, scores,
+                           masks, Sb, maxlen, a, keepbits, counts);
+    }
     return hipGetLastError();
 }
 
