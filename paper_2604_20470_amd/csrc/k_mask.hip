@@ -4,12 +4,13 @@
 //                density rule); one wavefront classifies one (query block, key block) pair,
 //                lanes own columns, ballots count active columns.
 //   k_select     one workgroup per (batch, mask, query block) row: compacts the selectable
-//                blocks into LDS as 64-bit sort keys, bitonic-sorts them, then takes the
-//                static top-k or the dynamic cumulative-mass prefix (paper Eq. 8 k rule;
-//                keep-one fallback of Eq. 11 / Algorithm 1).
-//                In the seeded uniform mode (Eq. 8 as worded in the paper) the sort key is a
+//                blocks into LDS as 64-bit keys (score descending, key block ascending), then
+//                static top-k: radix selection of the k-th smallest key, keep every key up to it
+//                (paper Eq. 8 k rule); dynamic: bitonic sort and the cumulative-mass prefix
+//                (keep-one fallback of Eq. 11 / Algorithm 1).
+//                In the seeded uniform mode (Eq. 8 as worded in the paper) the key is a
 //                counter-based hash of (seed, query block, key block) instead of the score.
-//   k_select_zscore  the paper's dynamic rule (Eqs. 10-11), one wavefront per row: lanes own candidate sets
+//   k_select_zscore  the paper's dynamic rule (Eqs. 10-11) per row: lanes own candidate sets
 //                (frame distance, side), standardise the scores of a set in fp64 and keep
 //                z >= tau_1 / tau_2, with the keep-one fallback.
 //   k_emit       per row: offset = sum of the previous rows' counts, bit-expansion to
@@ -135,6 +136,41 @@ __device__ __forceinline__ int keep_count(int n, double ratio) {
     return max(1, k);
 }
 
+// The k-th smallest (k = 1 .. n) of n distinct 64-bit keys in LDS: most-significant-digit-first radix selection,
+// eight bits per pass.  A pass counts, among the keys that agree with the digits fixed so far, how many fall in each
+// of the 256 values of the next digit (thread t owns bin t), scans the counts and descends into the bin that holds
+// rank k.  O(n) per pass instead of the O(n log^2 n) of a full sort: the static rules only need the set of the k
+// smallest keys, not their order.  All threads of the workgroup call it and all receive the key.
+__device__ uint64_t kth_smallest(const uint64_t* keys, int n, int k, uint32_t* hist, int* s_wave, int* s_pick) {
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    uint64_t prefix = 0ull, mask = 0ull;
+    int rank = k;
+    for (int shift = 56; shift >= 0; shift -= 8) {
+        hist[tid] = 0u;
+        __syncthreads();
+        for (int i = tid; i < n; i += kThreads) {
+            const uint64_t key = keys[i];
+            if ((key & mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        const int h = (int)hist[tid];
+        int incl = h;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        for (int i = 0; i < wave; ++i) incl += s_wave[i];
+        if (incl - h < rank && rank <= incl) { s_pick[0] = tid; s_pick[1] = rank - (incl - h); }
+        __syncthreads();
+        prefix |= (uint64_t)(uint32_t)s_pick[0] << shift;
+        mask |= 0xffull << shift;
+        rank = s_pick[1];
+    }
+    return prefix;
+}
+
 // grid: (Sb, masks, B).  LDS: keys[sort_cap] u64 | mass[sort_cap] f64 (dynamic mode) | keep[words] u32
 __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__ class_map,
                                                      const float* __restrict__ scores, int masks, int Sb,
@@ -169,7 +205,24 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
     }
     __syncthreads();
     const int n = s_n;
-    if (n > 0) {
+    if (n > 0 && a.mode != 1) {
+        // static top-k / seeded sample: keep the k smallest keys (with two ratios: the k_near smallest NEAR keys and the
+        // k_far smallest FAR keys; every NEAR key is below every FAR key)
+        __shared__ uint32_t s_hist[kThreads];
+        __shared__ int s_wave4[kWaves], s_pick[2];
+        const int n_near = a.two_ratio ? s_near : n;
+        const int k_near = keep_count(n_near, a.ratio);
+        const int k_far = a.two_ratio ? keep_count(n - n_near, a.ratio_far) : 0;
+        const uint64_t none = 0ull;
+        const uint64_t t_near = k_near > 0 ? kth_smallest(keys, n, k_near, s_hist, s_wave4, s_pick) : none;
+        const uint64_t t_far = k_far > 0 ? kth_smallest(keys, n, n_near + k_far, s_hist, s_wave4, s_pick) : none;
+        for (int i = tid; i < n; i += kThreads) {
+            const uint64_t key = keys[i];
+            const bool far_key = (key >> 63) != 0;
+            const bool sel = far_key ? (k_far > 0 && key <= t_far) : (k_near > 0 && key <= t_near);
+            if (sel) { const int kb = key_block(key); atomicOr(&keep[kb >> 5], 1u << (kb & 31)); }
+        }
+    } else if (n > 0) {
         int P = 1;
         while (P < n) P <<= 1;
         for (int i = n + tid; i < P; i += kThreads) keys[i] = ~0ull;
@@ -187,22 +240,7 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
                 __syncthreads();
             }
         }
-        if (a.mode != 1) {
-            if (a.two_ratio) {
-                const int n_near = s_near;
-                const int k_near = keep_count(n_near, a.ratio), k_far = keep_count(n - n_near, a.ratio_far);
-                for (int i = tid; i < n; i += kThreads) {
-                    const bool sel = (i < n_near) ? (i < k_near) : (i - n_near < k_far);
-                    if (sel) { const int kb = key_block(keys[i]); atomicOr(&keep[kb >> 5], 1u << (kb & 31)); }
-                }
-            } else {
-                const int k = keep_count(n, a.ratio);
-                for (int i = tid; i < k; i += kThreads) {
-                    const int kb = key_block(keys[i]);
-                    atomicOr(&keep[kb >> 5], 1u << (kb & 31));
-                }
-            }
-        } else {
+        {
             const double top = (double)key_score(keys[0]);
             for (int i = tid; i < n; i += kThreads) mass[i] = exp((double)key_score(keys[i]) - top);
             __syncthreads();
