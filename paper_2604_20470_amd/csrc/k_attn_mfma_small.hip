@@ -151,10 +151,13 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
                 dst[t][db] = u.v;
             }
     };
-    // init0 / init1: 0, or -inf for a half this wavefront does not own (its logits stay -inf, its probabilities 0)
+    // init0 / init1: 0, or -inf for a half this wavefront does not own (its logits stay -inf, its probabilities 0).
+    // The accumulation starts from -m_ref, so the matrix instruction delivers the logits relative to the exponent
+    // reference (the accumulators have to be initialised anyway; the Bs = 128 kernel keeps this vector in registers).
     v16f s[2];
+    const float c0 = init0 - st.m_ref, c1 = init1 - st.m_ref;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) { s[0][j] = init0; s[1][j] = init1; }
+    for (int j = 0; j < 16; ++j) { s[0][j] = c0; s[1][j] = c1; }
 #pragma unroll
     for (int batch = 0; batch < 2; ++batch) {
         v8bf kf[2][4];
@@ -179,11 +182,6 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
     read_v(MB0, vfa);                              // lands while the softmax runs
     __builtin_amdgcn_sched_barrier(0);
 
-    // logits relative to the exponent reference (this kernel keeps no -m_ref accumulator operand: 16 registers less)
-#pragma unroll
-    for (int mb = MB0; mb < MB1; ++mb)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) s[mb][j] -= st.m_ref;
     // keys past the end of the sequence (only in the last key block)
     if (valid0 < 32 || valid1 < 32) {
         int h4 = half * 4;
