@@ -273,6 +273,30 @@ def test_key_block_list_with_out_of_range_entries_is_clamped_not_followed():
     assert torch.equal(O_bad, O_good)
 
 
+@pytest.mark.parametrize("bs", [32, 64])
+def test_small_block_lists_with_out_of_range_and_repeated_entries(bs):
+    """Block sizes 32 / 64 merge the rows of a 128-token group first: out-of-range indices are clamped there, and a
+    key block listed twice in a row counts once (documented in the header)."""
+    import dataclasses
+    wl = dataclasses.replace(tiny_case("ragged128"), Bs=bs)
+    run = GpuRun(wl)
+    Sb = wl.Sb
+    rowptr = torch.arange(0, 3 * Sb + 1, 3, dtype=torch.int32, device="cuda").view(1, 1, -1).contiguous()
+    bad = torch.tensor([-5, Sb + 7, Sb + 9] * Sb, dtype=torch.int32, device="cuda").view(1, 1, -1)
+    rep = torch.tensor([0, Sb - 1, 0] * Sb, dtype=torch.int32, device="cuda").view(1, 1, -1)
+    rowptr2 = torch.arange(0, 2 * Sb + 1, 2, dtype=torch.int32, device="cuda").view(1, 1, -1).contiguous()
+    good = torch.tensor([0, Sb - 1] * Sb, dtype=torch.int32, device="cuda").view(1, 1, -1)
+    O_good = run.attention(rowptr2, good, 2 * Sb)
+    assert torch.equal(run.attention(rowptr, bad, 3 * Sb), O_good)
+    assert torch.equal(run.attention(rowptr, rep, 3 * Sb), O_good)
+    rp = rowptr2[0, 0].cpu().numpy().astype(np.int64)
+    ci = good[0, 0].cpu().numpy().astype(np.int64)
+    ref = o.masked_attention(to_f64(run.Qc[0, 0]), to_f64(run.Kc[0, 0]), to_f64(run.Vc[0, 0]), rp, ci, wl.Bs)
+    for qb, blk in ref.items():
+        got = to_f64(O_good[0, 0, qb * wl.Bs: qb * wl.Bs + blk.shape[0]])
+        assert float(np.abs(got - blk).max()) <= ATTN_TOL["bf16"]
+
+
 def _q_value_that_survives_prescaling(d):
     """A bf16 value q0 in [4, 16) for which q0 * log2(e)/sqrt(d) is (almost) a bf16 number again."""
     cs = np.float32(1.4426950408889634) / np.sqrt(np.float32(d))
