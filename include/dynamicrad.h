@@ -190,7 +190,9 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
  * bf16 inputs with d = 128 use bf16 MFMA (operands Q * log2(e)/sqrt(d) re-rounded to bf16, K,
  * V and the probabilities rounded to bf16) with fp32 accumulation and fp32 softmax, for every
  * block size; fp32 inputs, and bf16 inputs with d = 64, are computed in fp32 throughout.
- * Out-of-range key-block indices are clamped to [0, Sb) (memory safety), not reported; a row
+ * Out-of-range key-block indices are clamped to [0, Sb) and row ranges are clipped to
+ * [0, colidx_stride] (memory safety: a mask that overflowed its capacity is read as far as it
+ * was written), neither is reported; a row
  * whose list is not ascending is still summed correctly (softmax does not depend on the order).
  * A key block listed twice in one row is outside the contract (block sizes 32 and 64 count it
  * once, block size 128 once per listing).  For block sizes 32 and 64 the call first merges

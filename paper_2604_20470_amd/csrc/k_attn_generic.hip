@@ -62,7 +62,9 @@ __global__ __launch_bounds__(kThreads) void k_attn_generic(AttnArgs a) {
     const int mh = (a.mask_heads == 1) ? 0 : h;
     const int32_t* rp = a.rowptr + ((int64_t)b * a.mask_heads + mh) * (a.Sb + 1);
     const int32_t* ci = a.colidx + ((int64_t)b * a.mask_heads + mh) * a.colidx_stride;
-    const int beg = rp[qb], end = rp[qb + 1];
+    // row range, clipped to the colidx array of this mask (a list cut short by a too small capacity stays in bounds)
+    const int lim = (int)min(a.colidx_stride, (int64_t)0x7fffffff);
+    const int beg = min(max(rp[qb], 0), lim), end = min(max(rp[qb + 1], beg), lim);
 
     const bool row_ok = q_row0 + r < q_end;
     if (row_ok) load_row_to_lds<BF16>(Qp + (int64_t)(q_row0 + r) * row_bytes, sQ + r * D, D, g, 8);

@@ -264,8 +264,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int mh = (a.mask_heads == 1) ? 0 : h;
     const int32_t* rp = a.rowptr + ((int64_t)b * a.mask_heads + mh) * (a.Sb + 1);
     const int32_t* ci = a.colidx + ((int64_t)b * a.mask_heads + mh) * a.colidx_stride;
-    const int beg = __builtin_amdgcn_readfirstlane(rp[qb]);
-    const int end = __builtin_amdgcn_readfirstlane(rp[qb + 1]);
+    // row range, clipped to the colidx array of this mask (a list cut short by a too small capacity stays in bounds)
+    const int lim = (int)min(a.colidx_stride, (int64_t)0x7fffffff);
+    const int beg = min(max(__builtin_amdgcn_readfirstlane(rp[qb]), 0), lim);
+    const int end = min(max(__builtin_amdgcn_readfirstlane(rp[qb + 1]), beg), lim);
 
     const float cs = 1.4426950408889634f / sqrtf((float)kD);   // log2(e) / sqrt(d)
     // Q^T fragments (B operand of S^T = K Q^T): lane holds query l32, channels ks*16 + 8*half .. +7

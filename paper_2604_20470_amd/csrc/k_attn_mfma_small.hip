@@ -329,7 +329,8 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
     const int gmask = (a.mask_heads == 1) ? 0 : h;
     const int64_t gid = ((int64_t)b * a.mask_heads + gmask) * groups + qg;
     const int first_row = min(qg * L, a.Sb);
-    const int32_t* gl = a.gcol + ((int64_t)b * a.mask_heads + gmask) * a.colidx_stride + __builtin_amdgcn_readfirstlane(rp[first_row]);
+    const int64_t goff = min(max((int64_t)__builtin_amdgcn_readfirstlane(rp[first_row]), (int64_t)0), a.colidx_stride);   // as in k_group_union
+    const int32_t* gl = a.gcol + ((int64_t)b * a.mask_heads + gmask) * a.colidx_stride + goff;
     const int cnt = __builtin_amdgcn_readfirstlane(a.gcount[gid]);
     int pos = 0;
     int win = (cnt > 0) ? gl[min(lane, cnt - 1)] : 0;
@@ -455,14 +456,15 @@ __global__ __launch_bounds__(256) void k_group_union(const int32_t* __restrict__
     __syncthreads();
     const int row0 = min(g * L, Sb), row1 = min(g * L + L, Sb);
     for (int l = 0; l < row1 - row0; ++l) {
-        const int beg = rp[row0 + l], end = rp[row0 + l + 1];
+        const int lim = (int)min(colidx_stride, (int64_t)0x7fffffff);       // clipped to this mask's colidx array
+        const int beg = min(max(rp[row0 + l], 0), lim), end = min(max(rp[row0 + l + 1], beg), lim);
         for (int i = beg + tid; i < end; i += 256) {
             const int kb = min(max(ci[i], 0), Sb - 1);
             atomicOr(&pres[l * words + (kb >> 5)], 1u << (kb & 31));
         }
     }
     __syncthreads();
-    const int64_t off0 = rp[row0];
+    const int64_t off0 = min(max((int64_t)rp[row0], (int64_t)0), colidx_stride);
     int32_t* out = gcol + mask_id * colidx_stride + off0;
     const int64_t room = colidx_stride - off0;             // a well-formed CSR never needs more; a malformed one is cut
     int base = 0;

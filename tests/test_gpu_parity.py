@@ -121,6 +121,28 @@ def test_mask_capacity_overflow_is_reported_not_written():
     assert (colidx[0, 0] == colidx2[0, 0, :cap]).all()
 
 
+@pytest.mark.parametrize("case,bs", [("tiny8", 32), ("ragged128", 128), ("ragged128", 32), ("ragged128", 64)])
+def test_attention_reads_an_overflowed_mask_only_as_far_as_it_was_written(case, bs):
+    """A caller that ignores nnz > capacity: the row ranges are clipped to the colidx array, so the attention stage
+    stays in bounds and computes the attention of the truncated lists (rows past the cut: O = 0)."""
+    import dataclasses
+    wl = dataclasses.replace(tiny_case(case), Bs=bs)
+    run = GpuRun(wl)
+    scores = run.block_scores()
+    full_cap, _ = dr.dr_mask_capacity(run.ctx, run.shape, wl.lam, run.params)
+    cap = full_cap // 3
+    rowptr, colidx, nnz, _ = run.build_mask(scores, "static", 1.0, capacity=cap)
+    assert int(nnz[0, 0]) > cap
+    O = run.attention(rowptr, colidx, cap)
+    rp = np.minimum(rowptr[0, 0].cpu().numpy().astype(np.int64), cap)
+    ci = colidx[0, 0, :cap].cpu().numpy().astype(np.int64)
+    for h in range(len(run.heads)):
+        ref = o.masked_attention(to_f64(run.Qc[0, h]), to_f64(run.Kc[0, h]), to_f64(run.Vc[0, h]), rp, ci, wl.Bs)
+        for qb, blk in ref.items():
+            got = to_f64(O[0, h, qb * wl.Bs: qb * wl.Bs + blk.shape[0]])
+            assert float(np.abs(got - blk).max()) <= ATTN_TOL[wl.dtype], (h, qb)
+
+
 def _attention_check(run, rowptr, colidx, cap, heads_rows, tol):
     O, lse = run.attention(rowptr, colidx, cap, want_lse=True)
     wl = run.wl
