@@ -130,7 +130,7 @@ def main():
                     help="only run three plain 1 GiB device copies (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py: this build runs on one GPU only (the path shards by head with no exchange; see DESIGN.md); "
+        log("bench.py: this build runs on one GPU only (the path shards by head with no exchange inside it); "
             "--gpus must be 1")
         sys.exit(2)
 
