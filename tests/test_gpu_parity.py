@@ -295,6 +295,19 @@ def test_key_block_list_with_out_of_range_entries_is_clamped_not_followed():
     assert torch.equal(O_bad, O_good)
 
 
+@pytest.mark.parametrize("bs", [32, 64, 128])
+def test_mfma_paths_with_two_batch_elements(bs):
+    """B = 2 on the bf16 MFMA paths (the merged group lists and the masks are indexed by batch element)."""
+    wl = tiny_case("ragged128", Bs=bs, B=2)
+    every = [(b, h, None) for b in range(wl.B) for h in range(wl.H)]
+    for head_fuse in (2, 0):
+        run = GpuRun(wl, params=dr.MaskParams(gamma=3.0, head_fuse=head_fuse))
+        scores = run.block_scores()
+        rowptr, colidx, nnz, cap = run.build_mask(scores, "static", 0.3)
+        assert not torch.equal(colidx[0], colidx[1]) or int(nnz[0, 0]) == 0      # the two elements differ
+        _attention_check(run, rowptr, colidx, cap, every, ATTN_TOL[wl.dtype])
+
+
 @pytest.mark.parametrize("bs", [32, 64])
 def test_small_block_lists_with_out_of_range_and_repeated_entries(bs):
     """Block sizes 32 / 64 merge the rows of a 128-token group first: out-of-range indices are clamped there, and a
