@@ -250,9 +250,10 @@ def test_bad_arguments_are_rejected_on_the_host():
     run.build_mask(s, "static", 0.5)
 
 
-def test_strided_layout_batch_and_per_head_masks_on_the_mfma_path():
-    """[B, N, H, d] storage viewed as [B, H, N, d] (stride_n = H*d), B = 2, one mask per head, bf16/d=128/Bs=128."""
-    wl = tiny_case("ragged128", B=2, index=16)
+@pytest.mark.parametrize("bs", [128, 64, 32])
+def test_strided_layout_batch_and_per_head_masks_on_the_mfma_path(bs):
+    """[B, N, H, d] storage viewed as [B, H, N, d] (stride_n = H*d), B = 2, one mask per head, bf16 / d = 128."""
+    wl = tiny_case("ragged128", B=2, index=16, Bs=bs)
     run = GpuRun(wl, params=dr.MaskParams(head_fuse=0))
     for name in ("Q", "K", "V"):
         t = getattr(run, name)
