@@ -147,7 +147,9 @@ dr_status dr_block_scores(dr_ctx* ctx, const dr_shape* shape, const void* Q, con
  *             mu = mean, sigma = sqrt(mean (s - mu)^2), z = (s - mu) / (sigma + 1e-6);
  *             a block is kept when z >= tau, tau = `ratio_or_tau` for NEAR blocks and
  *             params->tau_far for FAR blocks (if has_tau_far); a set where nothing passes
- *             keeps its highest score (lower index on ties).
+ *             keeps its highest score (lower index on ties).  The kernel holds a row as a
+ *             tile of Nf x (ceil(Hg*Wg / Bs) + 1) scores in LDS: DR_ERR_UNSUPPORTED when that
+ *             exceeds 144 KB (beyond about a million tokens at block size 32).
  *   uniform : (Eq. 8 as the paper words it) scores are not read (`scores` may be NULL);
  *             every NEAR/FAR block gets the 32-bit key
  *             fmix32(fmix32(seed ^ fmix32(qb)) + kb), fmix32 = MurmurHash3's finaliser;

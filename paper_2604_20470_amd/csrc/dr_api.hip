@@ -317,10 +317,14 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
     if ((!scores && mode != DR_MODE_UNIFORM_RATIO) || !rowptr || !colidx || !nnz)
         return fail(ctx, DR_ERR_INVALID_ARG, "NULL output or scores pointer");
     if (colidx_capacity <= 0) return fail(ctx, DR_ERR_CAPACITY, "colidx_capacity must be > 0");
+    const int Sb = (shape->N + shape->Bs - 1) / shape->Bs;
+    if (mode == DR_MODE_ZSCORE_THRESHOLD &&
+        select_zscore_lds_bytes(Sb, shape->Hg * shape->Wg, shape->Nf, shape->Bs) > kSelectZscoreMaxLds)
+        return fail(ctx, DR_ERR_UNSUPPORTED, "z-score mode: a row tile of %d frames x %d key blocks per frame exceeds the LDS",
+                    shape->Nf, (shape->Hg * shape->Wg + shape->Bs - 1) / shape->Bs + 1);
     DeviceGuard g(ctx->device);
     hipStream_t s = (hipStream_t)stream;
     if ((st = ensure_geometry(ctx, shape, lambda, p, s)) != DR_OK) return st;
-    const int Sb = (shape->N + shape->Bs - 1) / shape->Bs;
     const int masks = p->head_fuse > 0 ? 1 : shape->H;
     if (ctx->max_sel > kMaxSelectablePerRow)
         return fail(ctx, DR_ERR_UNSUPPORTED, "%d selectable blocks in a row exceed %d", ctx->max_sel, kMaxSelectablePerRow);

@@ -55,7 +55,12 @@ struct SelectArgs {
 // keepbits[(b*masks+m)*Sb + qb][words], counts[(b*masks+m)*Sb + qb]
 hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
                          const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
-// z-score mode (paper Eqs. 10-11 at block level); same outputs as launch_select
+// z-score mode (paper Eqs. 10-11 at block level); same outputs as launch_select.  Its kernel holds one row's scores
+// in LDS as a [key blocks per frame + 1][Nf] tile beside the keep bitmap: geometries beyond the limit are refused.
+constexpr size_t kSelectZscoreMaxLds = 144 * 1024;
+inline size_t select_zscore_lds_bytes(int Sb, int Nt, int Nf, int Bs) {
+    return (size_t)((Sb + 31) / 32) * 4 + (size_t)((Nt + Bs - 1) / Bs + 1) * (size_t)Nf * 4;
+}
 hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
                                 const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
 hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb, bool shared,

@@ -277,11 +277,11 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
 // grid: (Sb, masks, B).  A candidate set of the row is identified by the frame f that realises its gap: the key
 // blocks whose first frame is f (f after the query block) or whose last frame is f (f before it); they lie in the
 // key-block range of frame f, at most `maxlen` blocks.
-// TILED (LDS: keep[words] u32 | tile[maxlen][Nf] f32): all threads first scatter the row's selectable scores into
-// the tile, position inside the set's range major, frame minor (reads of the row coalesced, the frame arithmetic once
-// per key block); a lane then walks "its" frame's column: neighbouring lanes read neighbouring LDS words, and nothing
-// in the serial part touches global memory.  Cells that hold no member keep a sentinel (a NaN pattern; scores are
-// finite).  Without TILED (tile too large for LDS) a lane reads its range from global memory.
+// LDS: keep[words] u32 | tile[maxlen][Nf] f32.  All threads first scatter the row's selectable scores into the tile,
+// position inside the set's range major, frame minor (reads of the row coalesced, the frame arithmetic once per key
+// block); a lane then walks "its" frame's column: neighbouring lanes read neighbouring LDS words, and nothing in the
+// serial part touches global memory.  Cells that hold no member keep a sentinel (a NaN pattern; scores are finite).
+// The host refuses geometries whose tile does not fit the LDS (beyond about a million tokens at block size 32).
 // The three passes over a set run in ascending key-block order, one addition at a time, with floating-point
 // contraction off: the summation order and the absence of fused multiply-adds are part of the definition the
 // results are compared against.  A cell outside the set adds +0.0, which leaves the running sums bit for bit as they
@@ -291,7 +291,6 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
 // only when the estimate lies within 2^-50 |tau| of tau is the division itself evaluated.
 constexpr uint32_t kNoMember = 0x7fc0dead;
 
-template <bool TILED>
 __global__ __launch_bounds__(kThreads) void k_select_zscore(const uint8_t* __restrict__ class_map,
                                                             const float* __restrict__ scores, int masks, int Sb,
                                                             int maxlen, SelectArgs a, uint32_t* __restrict__ keepbits,
@@ -309,15 +308,14 @@ __global__ __launch_bounds__(kThreads) void k_select_zscore(const uint8_t* __res
     const uint8_t* crow = class_map + (int64_t)qb * Sb;
     for (int i = tid; i < words; i += kThreads) keep[i] = 0u;
     if (tid == 0) s_cnt = 0;
-    if (TILED)
-        for (int i = tid; i < maxlen * a.Nf; i += kThreads) tile[i] = kNoMember;
+    for (int i = tid; i < maxlen * a.Nf; i += kThreads) tile[i] = kNoMember;
     __syncthreads();
     const int r0 = qb * a.Bs, r1 = min(a.N, r0 + a.Bs);
     const int i0 = r0 / a.Nt, i1 = (r1 - 1) / a.Nt;
     for (int kb = tid; kb < Sb; kb += kThreads) {
         const int c = crow[kb];
         if (c == 3) atomicOr(&keep[kb >> 5], 1u << (kb & 31));
-        if (TILED && (c == 1 || c == 2)) {
+        if (c == 1 || c == 2) {
             const uint32_t c0 = (uint32_t)kb * (uint32_t)a.Bs;                   // < N <= 2^31 - 1: 32-bit divisions
             const int j0 = (int)(c0 / (uint32_t)a.Nt);
             const int j1 = (int)((min((uint32_t)a.N, c0 + (uint32_t)a.Bs) - 1u) / (uint32_t)a.Nt);
@@ -326,7 +324,7 @@ __global__ __launch_bounds__(kThreads) void k_select_zscore(const uint8_t* __res
             tile[pos * a.Nf + f] = __float_as_uint(srow[kb]);
         }
     }
-    if (TILED) __syncthreads();
+    __syncthreads();
     for (int f = tid; f < a.Nf; f += kThreads) {
         const bool after = f > i1 + 1, before = f < i0 - 1;                      // gaps 0 and 1 are the never-pruned zone
         if (!after && !before) continue;
@@ -335,13 +333,7 @@ __global__ __launch_bounds__(kThreads) void k_select_zscore(const uint8_t* __res
         const int kb_lo = (int)(f_lo / a.Bs);
         const int len = min(Sb - 1, (int)((f_hi - 1) / a.Bs)) - kb_lo + 1;
         // cell p of the set: score bits, or kNoMember
-        auto cell = [&](int p) -> uint32_t {
-            if (TILED) return tile[p * a.Nf + f];
-            const int kb = kb_lo + p, c = crow[kb];
-            const int64_t c0 = (int64_t)kb * a.Bs;
-            const int64_t edge = after ? c0 : min((int64_t)a.N, c0 + a.Bs) - 1;
-            return ((c == 1 || c == 2) && edge >= f_lo && edge < f_hi) ? __float_as_uint(srow[kb]) : kNoMember;
-        };
+        auto cell = [&](int p) -> uint32_t { return tile[p * a.Nf + f]; };
         int n = 0;
         double sum = 0.0;
 #pragma unroll 4
@@ -474,21 +466,16 @@ hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, i
 
 hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
                                 const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s) {
-    const size_t words = (Sb + 31) / 32;
-    const int maxlen = (a.Nt + a.Bs - 1) / a.Bs + 1;          // key blocks that can touch one frame
-    const size_t tiled = words * 4 + (size_t)maxlen * a.Nf * 4;
-    if (tiled <= 144 * 1024) {
-        if (tiled > 64 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_zscore<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)tiled);
-            if (e != hipSuccess) return e;
-        }
-        hipLaunchKernelGGL(k_select_zscore<true>, dim3(Sb, masks, B), dim3(kThreads), tiled, s, class_map, scores, masks,
-                           Sb, maxlen, a, keepbits, counts);
-    } else {
-        hipLaunchKernelGGL(k_select_zscore<false>, dim3(Sb, masks, B), dim3(kThreads), words * 4, s, class_map, scores,
-                           masks, Sb, maxlen, a, keepbits, counts);
+    const size_t lds = select_zscore_lds_bytes(Sb, a.Nt, a.Nf, a.Bs);
+    if (lds > kSelectZscoreMaxLds) return hipErrorInvalidValue;      // the host layer checks this before calling
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_zscore),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
     }
+    const int maxlen = (a.Nt + a.Bs - 1) / a.Bs + 1;          // key blocks that can touch one frame
+    hipLaunchKernelGGL(k_select_zscore, dim3(Sb, masks, B), dim3(kThreads), lds, s, class_map, scores, masks, Sb, maxlen,
+                       a, keepbits, counts);
     return hipGetLastError();
 }
 
