@@ -123,3 +123,48 @@ def test_small_block_sizes_full(name, bs):
     sample = [(0, hi, _sample_rows(wl, rng, 4)) for hi in (0, 2)]
     worst = _attention_check(run, rowptr, colidx, cap, sample, ATTN_TOL[wl.dtype])
     print(f"[{name} Bs={bs}] attention max-abs err {worst:.3e} on {sample}", flush=True)
+
+
+def test_micro_benchmark_shape_every_rule_on_sampled_rows():
+    """264 000 tokens at block size 32 (8250 key blocks per row, up to several thousand selectable ones): the long-row
+    code paths of the selection kernels (large sort, radix selection over long rows, the full-width z-score tile).
+    Scores in full; the five rules on 150 sampled rows, bit for bit, the oracle selecting from the GPU's scores."""
+    wl = CONFIGS["micro264k"]
+    rng = np.random.default_rng(264)
+    run = GpuRun(wl, heads=[0, 1], params=dr.MaskParams(tau_far=0.8, ratio_far=0.02, seed=7))
+    cls = oracle_class_map(wl)
+    gs = o.block_frame_gap(wl.N, wl.Nt, wl.Bs)
+    scores = run.block_scores()
+    want = o.block_scores(to_f64(run.Qc[:, :2]), to_f64(run.Kc[:, :2]), wl.Bs, 2)
+    assert score_error(scores, want) <= SCORE_TOL
+    s_host = scores[0, 0].cpu().numpy()
+    rows = sorted(set(_sample_rows(wl, rng, 140)) | {wl.Sb // 2, 249, 250, 251})
+    n_sel = ((cls == 1) | (cls == 2)).sum(axis=1)
+    print(f"[micro264k] selectable per row: max {int(n_sel.max())}, sampled max {int(n_sel[rows].max())}", flush=True)
+
+    def check(mode, par, pick):
+        rowptr, colidx, nnz, cap = run.build_mask(None if mode == "uniform" else scores, mode, par)
+        rp = rowptr[0, 0].cpu().numpy().astype(np.int64)
+        ci = colidx[0, 0].cpu().numpy()
+        assert rp[-1] == int(nnz[0, 0]) <= cap
+        for qb in rows:
+            got = ci[rp[qb]:rp[qb + 1]]
+            assert np.array_equal(got, pick(qb)), (mode, qb)
+        print(f"[micro264k] {mode}: nnz={rp[-1]} sparsity={1 - rp[-1] / wl.Sb ** 2:.4f}", flush=True)
+
+    check("static", 0.1, lambda qb: o.select_static(s_host[qb], cls[qb], 0.1, 0.02))
+    check("dynamic", 0.9, lambda qb: o.select_dynamic(s_host[qb], cls[qb], 0.9))
+    check("zscore", 0.3, lambda qb: o.select_zscore(s_host[qb], cls[qb], gs[0][qb], gs[1][qb], 0.3, 0.8))
+    check("uniform", 0.1, lambda qb: o.select_uniform(qb, cls[qb], 0.1, 0.02, 7))
+    run.params = dr.MaskParams(seed=7)                      # one ratio for NEAR and FAR together
+    check("static", 0.35, lambda qb: o.select_static(s_host[qb], cls[qb], 0.35, None))
+    # gamma = 3 widens the windows: rows of several thousand selectable blocks (sort area beyond 64 KB of LDS)
+    run.params = dr.MaskParams(gamma=3.0, seed=7)
+    cls = oracle_class_map(wl, gamma=3.0)
+    n_sel = ((cls == 1) | (cls == 2)).sum(axis=1)
+    rows = sorted({0, wl.Sb - 1, int(np.argmax(n_sel))} | set(rng.integers(0, wl.Sb, 12).tolist()))
+    print(f"[micro264k gamma=3] selectable per row: max {int(n_sel.max())}", flush=True)
+    assert int(n_sel.max()) > 4096
+    check("dynamic", 0.9, lambda qb: o.select_dynamic(s_host[qb], cls[qb], 0.9))
+    check("static", 0.2, lambda qb: o.select_static(s_host[qb], cls[qb], 0.2, None))
+    check("zscore", 0.3, lambda qb: o.select_zscore(s_host[qb], cls[qb], gs[0][qb], gs[1][qb], 0.3, 0.3))
