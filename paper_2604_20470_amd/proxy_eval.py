@@ -14,6 +14,8 @@ import numpy as np
 
 from . import binding as dr
 
+MODE_TOKENS = -1     # proxy_loss: build the mask with Algorithm 1 in its own order (token links, then aggregation)
+
 
 def attention_matrix(ctx: dr.Context, shape: dr.Shape, Q, K, rowptr, colidx, mask_heads: int, capacity: int):
     """A[b, h, p, q] under the block CSR, float32 torch tensor on Q's device.  Q, K: [B, H, N, d] float32."""
@@ -37,7 +39,7 @@ def attention_matrix(ctx: dr.Context, shape: dr.Shape, Q, K, rowptr, colidx, mas
 def proxy_loss(ctx: dr.Context, Q, K, Nf: int, Hg: int, Wg: int, Bs: int, mode: int, ratio_or_tau: float, lam: float,
                params: dr.MaskParams, target: float = 0.80, alpha: float = 10.0) -> Tuple[float, float, float]:
     """(loss, normalised squared error, effective sparsity) of one configuration on given features, averaged over
-    (batch, head): ||A_dense - A_sparse||_F^2 / ||A_dense||_F^2 + alpha * max(0, target - sparsity)."""
+    (batch, head); `mode` is one of the library's selection rules or MODE_TOKENS: ||A_dense - A_sparse||_F^2 / ||A_dense||_F^2 + alpha * max(0, target - sparsity)."""
     import torch
     B, H, N, d = Q.shape
     shape = dr.shape_of(Q, Nf, Hg, Wg, Bs)
@@ -48,8 +50,13 @@ def proxy_loss(ctx: dr.Context, Q, K, Nf: int, Hg: int, Wg: int, Bs: int, mode: 
     rowptr = torch.empty((B, masks, Sb + 1), dtype=torch.int32, device=Q.device)
     colidx = torch.empty((B, masks, cap), dtype=torch.int32, device=Q.device)
     nnz = torch.empty((B, masks), dtype=torch.int64, device=Q.device)
-    dr.dr_block_scores(ctx, shape, Q, K, params.head_fuse, scores)
-    dr.dr_build_mask(ctx, shape, mode, ratio_or_tau, lam, params, scores, rowptr, colidx, cap, nnz)
+    if mode == MODE_TOKENS:          # ratio_or_tau is tau_1; tau_2 comes from params
+        tscores = torch.empty((B, masks, N, N), dtype=torch.float32, device=Q.device)
+        dr.dr_token_scores(ctx, shape, Q, K, params.head_fuse, tscores)
+        dr.dr_build_mask_tokens(ctx, shape, ratio_or_tau, lam, params, tscores, rowptr, colidx, cap, nnz)
+    else:
+        dr.dr_block_scores(ctx, shape, Q, K, params.head_fuse, scores)
+        dr.dr_build_mask(ctx, shape, mode, ratio_or_tau, lam, params, scores, rowptr, colidx, cap, nnz)
     A_sparse = attention_matrix(ctx, shape, Q, K, rowptr, colidx, masks, cap)
     # dense reference through the same kernel: the all-ones block mask
     full_rp = (torch.arange(Sb + 1, dtype=torch.int32, device=Q.device) * Sb).view(1, 1, -1).repeat(B, 1, 1).contiguous()

@@ -37,3 +37,30 @@ def test_proxy_objective_matches_the_oracle(delta):
         assert abs(sparsity - o.effective_sparsity(rp, shape.Sb)) < 1e-12
         assert abs(nmse - want_nmse) <= 1e-5 * max(1.0, want_nmse), (mode, nmse, want_nmse)
         assert abs(loss - want_loss) <= 1e-5 * max(1.0, want_loss)
+
+
+def test_proxy_objective_with_the_token_level_mask():
+    """The same objective with the mask built by Algorithm 1 in its own order (token links, then aggregation)."""
+    Nf, Hg, Wg, D, Bs = 8, 8, 8, 64, 32
+    Nt, N = Hg * Wg, Nf * Hg * Wg
+    h = make_ar1_proxy(Nf, Nt, D, 0.15, seed=11)
+    Q = torch.from_numpy(h).view(1, 1, N, D).cuda()
+    ctx = dr.Context(0)
+    tab = o.frame_table(Nf, Nt, Bs, 2.0, 1.0)
+    hd = h.astype(np.float64)
+    A_dense = o.attention_matrix(hd, hd)
+    shape = dr.shape_of(Q, Nf, Hg, Wg, Bs)
+    tscores = torch.empty((1, 1, N, N), dtype=torch.float32, device="cuda")
+    dr.dr_token_scores(ctx, shape, Q, Q, 1, tscores)
+    seen = set()
+    for tau in (-0.5, 0.5, 1.5):
+        params = dr.MaskParams(gamma=2.0, head_fuse=1)
+        loss, nmse, sparsity = proxy_eval.proxy_loss(ctx, Q, Q, Nf, Hg, Wg, Bs, proxy_eval.MODE_TOKENS, tau, 1.0, params)
+        rp, ci = o.build_mask_from_tokens(tscores.cpu().numpy(), N, Nt, Bs, tab, 0.15, 0.60, tau)[0][0]
+        want_loss, want_nmse = o.proxy_loss(A_dense, o.attention_matrix(hd, hd, rp, ci, Bs),
+                                            o.effective_sparsity(rp, shape.Sb))
+        assert abs(sparsity - o.effective_sparsity(rp, shape.Sb)) < 1e-12
+        assert abs(nmse - want_nmse) <= 1e-5 * max(1.0, want_nmse), (tau, nmse, want_nmse)
+        assert abs(loss - want_loss) <= 1e-5 * max(1.0, want_loss)
+        seen.add(int(rp[-1]))
+    assert len(seen) > 1, "the thresholds must change the mask"
