@@ -23,6 +23,10 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work on it and return without a host synchronisation,
  *     except where a call says otherwise (first use of a new geometry).
+ *   - After one call with a given shape and parameters (which sizes the context's
+ *     scratch and builds the cached geometry) the stage calls only enqueue kernels on
+ *     `stream`: no allocation, no host synchronisation, no memset; such a sequence
+ *     can be captured in a HIP graph and replayed.
  *   - Every call returns a dr_status; nothing is thrown across the boundary.
  *     dr_last_error(ctx) returns the text of the last failure on that context.
  *     Argument errors are detected on the host before anything is launched.
