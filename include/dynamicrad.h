@@ -26,7 +26,9 @@
  *   - After one call with a given shape and parameters (which sizes the context's
  *     scratch and builds the cached geometry) the stage calls only enqueue kernels on
  *     `stream`: no allocation, no host synchronisation, no memset; such a sequence
- *     can be captured in a HIP graph and replayed.
+ *     can be captured in a HIP graph and replayed.  A replay reads the context's caches
+ *     (candidate geometry, uniform-rule selection) as they are then: keep a context whose
+ *     calls are captured to one geometry and one set of parameters.
  *   - Every call returns a dr_status; nothing is thrown across the boundary.
  *     dr_last_error(ctx) returns the text of the last failure on that context.
  *     Argument errors are detected on the host before anything is launched.
