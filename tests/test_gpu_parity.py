@@ -32,6 +32,8 @@ def _small_cases():
         tiny_case("ragged"),
         tiny_case("ragged128"),
         tiny_case("ragged", Bs=64, d=128, dtype="bf16", index=15),
+        tiny_case("tiny8", dtype="bf16", index=17),                   # bf16 storage at d = 64: the fp32-arithmetic kernel
+        tiny_case("ragged128", dtype="f32", index=18),                # fp32 storage at d = 128
     ]
 
 
