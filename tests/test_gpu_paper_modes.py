@@ -120,15 +120,3 @@ def test_paper_mode_arguments_are_checked():
     with pytest.raises(dr.DRError):
         run.build_mask(scores, "zscore", 0.5)
 
-
-def test_zscore_mode_refuses_a_row_tile_beyond_the_lds():
-    """200 frames of 80 x 100 tokens at block size 32: the row tile (200 x 251 scores) does not fit the LDS.  The
-    refusal comes from the host check, before any device work (the dummy pointers are never used)."""
-    wl = tiny_case("tiny8")
-    run = GpuRun(wl)
-    big = dr.Shape.from_buffer_copy(run.shape)
-    big.Nf, big.Hg, big.Wg, big.Bs = 200, 80, 100, 32
-    big.N = 200 * 8000
-    dummy = torch.zeros(16, dtype=torch.float32, device="cuda")
-    with pytest.raises(dr.DRError, match="LDS"):
-        dr.dr_build_mask(run.ctx, big, dr.MODE_ZSCORE, 0.5, 1.0, None, dummy, dummy, dummy, 16, dummy)

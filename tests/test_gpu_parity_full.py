@@ -168,3 +168,19 @@ def test_micro_benchmark_shape_every_rule_on_sampled_rows():
     check("dynamic", 0.9, lambda qb: o.select_dynamic(s_host[qb], cls[qb], 0.9))
     check("static", 0.2, lambda qb: o.select_static(s_host[qb], cls[qb], 0.2, None))
     check("zscore", 0.3, lambda qb: o.select_zscore(s_host[qb], cls[qb], gs[0][qb], gs[1][qb], 0.3, 0.3))
+
+
+def test_zscore_masks_in_full_at_24_frames_block_32():
+    """24 frames of 40 x 80 tokens at block size 32 (2400 key blocks per row, candidate sets of up to 101 blocks): the
+    z-score rule's masks in full, bit for bit, fused and per head."""
+    from workloads import Workload
+    wl = Workload("f24b32", 41, 1, 2, 128, 24, 40, 80, 32, "bf16", "field", "dynamic", 0.5, 0.9, 0.7)
+    cls = oracle_class_map(wl, gamma=2.0)
+    gs = o.block_frame_gap(wl.N, wl.Nt, wl.Bs)
+    for head_fuse, tau, tau_far in ((2, 0.3, 0.8), (0, -0.5, None)):
+        run = GpuRun(wl, params=dr.MaskParams(gamma=2.0, head_fuse=head_fuse, tau_far=tau_far))
+        scores = run.block_scores()
+        rowptr, colidx, nnz, cap = run.build_mask(scores, "zscore", tau)
+        want = o.build_mask(scores.cpu().numpy(), cls, "zscore", tau, gap_side=gs, tau_far=tau_far)
+        assert_masks_equal(rowptr, colidx, nnz, want)
+        print(f"[24 frames Bs=32, head_fuse={head_fuse}] nnz={int(nnz[0, 0])} of {int((cls != 0).sum())} candidates", flush=True)
