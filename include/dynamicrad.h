@@ -251,27 +251,26 @@ dr_status dr_build_mask_tokens(dr_ctx* ctx, const dr_shape* shape, double tau_ne
                                const dr_mask_params* params, const float* token_scores, int32_t* rowptr,
                                int32_t* colidx, int64_t colidx_capacity, int64_t* nnz, uint8_t* links, void* stream);
 
-/* Measurement aid (not a step of the method): average shader clock over a window.
- * Enqueues a one-wavefront kernel on `stream` that polls the constant 100 MHz counter for
- * `window_us` microseconds (1 .. 2 000 000) and then writes two uint64 to the device buffer
- * `out`: out[0] = shader-clock ticks elapsed, out[1] = 100 MHz ticks elapsed, so that
- * 100 * out[0] / out[1] is the mean shader clock in MHz over the window.  Run on a second
- * stream beside the attention kernel it reports the clock the chip sustains under that load;
- * the matrix-core peak the roofline is priced against assumes 2400 MHz.  Asynchronous; the
- * caller synchronises `stream` before reading `out`.  Errors: DR_ERR_INVALID_ARG for a NULL
- * pointer or a window out of range. */
-dr_status dr_clock_probe(dr_ctx* ctx, uint64_t window_us, uint64_t* out, void* stream);
-
-/* Measurement aid (not a step of the method): an MFMA-only loop, to price the attention kernel against what the
- * matrix cores of this device sustain rather than against the data-sheet peak alone.  Enqueues `workgroups`
- * workgroups of 4 wavefronts, each issuing iters * 8 matrix instructions (iters a multiple of 8) on register
- * operands and eight independent accumulators: shape 32 = v_mfma_f32_32x32x16_bf16 (32768 flop each), shape 16 =
- * v_mfma_f32_16x16x32_bf16 (16384 flop each).  Operands are one repeated value (random_operands = 0) or
- * pseudo-random bf16 numbers in [-1, 1) (1; the switching activity of real data).  `sink` is a device float the
- * kernel may write; *flop (host, optional) receives the flop count of the launch.  The caller times the launch
- * with events on `stream`.  Errors: DR_ERR_INVALID_ARG. */
-dr_status dr_mfma_probe(dr_ctx* ctx, int32_t shape, int32_t workgroups, int32_t iters, int32_t random_operands,
-                        float* sink, double* flop, void* stream);
+/*
+ * Objective of the paper's offline parameter search on its proxy task (App. C, Eq. 22), as a device reduction:
+ *   nmse     = mean over (b, h) of ||A_dense - A_sparse||_F^2 / ||A_dense||_F^2
+ *   sparsity = 1 - mean over (b, mask) of nnz / Sb^2      (effective sparsity: pruned fraction of block pairs)
+ *   loss     = nmse + alpha * max(0, target - sparsity)
+ * The attention matrices are inputs (the hot path does not materialise them; a caller reads them off
+ * dr_sparse_attn_fwd with one-hot V columns).
+ *   A_dense, A_sparse  device, float32, contiguous [B, H, N, N]
+ *   nnz        device int64 [B, masks] as written by dr_build_mask / dr_build_mask_tokens
+ *   Sb         number of blocks per side (> 0)
+ *   target, alpha      sparsity target and penalty weight of Eq. 22 (the paper uses 0.80 and 10)
+ *   out        device float64 [3]: loss, nmse, sparsity
+ * All sums are taken in fp64 in a fixed order (per (b, h): one workgroup, each thread over a strided subset, then a
+ * tree over the threads), so the result is reproducible run to run.  A (b, h) slice with ||A_dense||_F = 0
+ * contributes 0.  Asynchronous on `stream`; allocates nothing.  Errors: DR_ERR_INVALID_ARG for NULL pointers or
+ * non-positive sizes.
+ */
+dr_status dr_proxy_loss(dr_ctx* ctx, const float* A_dense, const float* A_sparse, int32_t B, int32_t H, int32_t N,
+                        const int64_t* nnz, int32_t masks, int32_t Sb, double target, double alpha, double* out,
+                        void* stream);
 
 /* Library version string, e.g. "dynamicrad-gfx950 0.2". */
 const char* dr_version(void);

@@ -74,9 +74,10 @@ def load_library():
     lib.dr_sparse_attn_fwd.argtypes = [vp, shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.dr_token_scores.argtypes = [vp, shp, vp, vp, i32, vp, vp]
     lib.dr_build_mask_tokens.argtypes = [vp, shp, f64, f64, mpp, vp, vp, vp, i64, vp, vp, vp]
+    lib.dr_proxy_loss.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, i32, f64, f64, vp, vp]
     lib.dr_clock_probe.argtypes = [vp, C.c_uint64, vp, vp]
     lib.dr_mfma_probe.argtypes = [vp, i32, i32, i32, i32, vp, C.POINTER(f64), vp]
-    for name in ("dr_token_scores", "dr_build_mask_tokens", "dr_clock_probe", "dr_mfma_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
+    for name in ("dr_token_scores", "dr_build_mask_tokens", "dr_proxy_loss", "dr_clock_probe", "dr_mfma_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
                  "dr_sparse_attn_fwd"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -177,6 +178,13 @@ def dr_build_mask_tokens(ctx: Context, shape: Shape, tau_near: float, lam: float
     ctx.check(ctx._lib.dr_build_mask_tokens(ctx._h, C.byref(shape), float(tau_near), float(lam), _pp(params),
                                             _ptr(token_scores), _ptr(rowptr), _ptr(colidx), int(colidx_capacity),
                                             _ptr(nnz), _ptr(links), _stream(stream)))
+
+
+def dr_proxy_loss(ctx: Context, A_dense, A_sparse, nnz, Sb: int, target: float, alpha: float, out, stream=None):
+    """Enqueue the proxy objective: A_dense, A_sparse float32 [B, H, N, N]; nnz int64 [B, masks]; out float64 [3]."""
+    B, H, N, _ = A_dense.shape
+    ctx.check(ctx._lib.dr_proxy_loss(ctx._h, _ptr(A_dense), _ptr(A_sparse), int(B), int(H), int(N), _ptr(nnz),
+                                     int(nnz.shape[1]), int(Sb), float(target), float(alpha), _ptr(out), _stream(stream)))
 
 
 def dr_clock_probe(ctx: Context, window_us: int, out, stream=None):

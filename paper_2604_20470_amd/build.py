@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdynamicrad.so")
-SOURCES = ["dr_api.hip", "k_scores.hip", "k_mask.hip", "k_attn_generic.hip", "k_attn_mfma.hip", "k_attn_mfma_small.hip", "k_tokens.hip", "k_clock_probe.hip"]
+SOURCES = ["dr_api.hip", "k_scores.hip", "k_mask.hip", "k_attn_generic.hip", "k_attn_mfma.hip", "k_attn_mfma_small.hip", "k_tokens.hip", "k_proxy.hip", "k_clock_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -22,7 +22,8 @@ def build(verbose: bool = False, force: bool = True) -> str:
     """Compile every source and link the shared library.  Returns the library path."""
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    headers = [os.path.join(CSRC, "dr_internal.h"), os.path.join(HERE, "..", "include", "dynamicrad.h")]
+    headers = [os.path.join(CSRC, "dr_internal.h"), os.path.join(HERE, "..", "include", "dynamicrad.h"),
+               os.path.join(HERE, "..", "include", "dynamicrad_probe.h")]
     hdr_time = max(os.path.getmtime(h) for h in headers)
 
     def compile_one(src):

@@ -1,6 +1,7 @@
 // Host layer of the DynamicRad library: argument validation, the fp64 per-t table of the
 // radial window and split rule (paper Eqs. 1-6), scratch management and kernel launches.
 #include "../../include/dynamicrad.h"
+#include "../../include/dynamicrad_probe.h"
 #include "dr_internal.h"
 
 #include <cmath>
@@ -31,6 +32,9 @@ struct dr_ctx {
     size_t uni_keep_bytes = 0, uni_count_bytes = 0;
     bool uni_valid = false;
     struct UniKey { double ratio, ratio_far; uint32_t seed; int32_t pad; } uni_key{};
+    // proxy objective: per (b, h) and slice partial sums
+    double* proxy_partial = nullptr;
+    size_t proxy_bytes = 0;
     // token-level order: link bytes [B, masks, N, N] when the caller does not ask for them
     uint8_t* links = nullptr;
     size_t links_bytes = 0;
@@ -234,7 +238,7 @@ void dr_destroy(dr_ctx* ctx) {
     {
         DeviceGuard g(ctx->device);
         void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->row_sel, ctx->totals, ctx->gcol,
-                        ctx->gcount, ctx->uni_keep, ctx->uni_counts, ctx->links};
+                        ctx->gcount, ctx->uni_keep, ctx->uni_counts, ctx->links, ctx->proxy_partial};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
     }
@@ -477,6 +481,23 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
     return DR_OK;
 }
 
+dr_status dr_proxy_loss(dr_ctx* ctx, const float* A_dense, const float* A_sparse, int32_t B, int32_t H, int32_t N,
+                        const int64_t* nnz, int32_t masks, int32_t Sb, double target, double alpha, double* out,
+                        void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    if (!A_dense || !A_sparse || !nnz || !out) return fail(ctx, DR_ERR_INVALID_ARG, "NULL pointer");
+    if (B <= 0 || H <= 0 || N <= 0 || masks <= 0 || Sb <= 0) return fail(ctx, DR_ERR_INVALID_ARG, "non-positive size");
+    if ((int64_t)B * H > 65535) return fail(ctx, DR_ERR_UNSUPPORTED, "B * H too large for the launch grid");
+    if (std::isnan(target) || std::isnan(alpha)) return fail(ctx, DR_ERR_INVALID_ARG, "target or alpha is NaN");
+    DeviceGuard g(ctx->device);
+    dr_status st;
+    const size_t need = (size_t)B * H * kProxySlices * 2 * sizeof(double);
+    if ((st = grow(ctx, (void**)&ctx->proxy_partial, &ctx->proxy_bytes, need)) != DR_OK) return st;
+    DR_HIP(ctx, launch_proxy_loss(A_dense, A_sparse, B * H, N, nnz, B * masks, Sb, target, alpha, ctx->proxy_partial, out,
+                                  (hipStream_t)stream));
+    return DR_OK;
+}
+
 dr_status dr_clock_probe(dr_ctx* ctx, uint64_t window_us, uint64_t* out, void* stream) {
     if (!ctx) return DR_ERR_INVALID_ARG;
     if (!out) return fail(ctx, DR_ERR_INVALID_ARG, "NULL output pointer");
@@ -493,6 +514,9 @@ dr_status dr_mfma_probe(dr_ctx* ctx, int32_t shape, int32_t workgroups, int32_t 
     if (shape != 32 && shape != 16) return fail(ctx, DR_ERR_INVALID_ARG, "shape must be 32 (32x32x16) or 16 (16x16x32)");
     if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || iters > (1 << 24) || (iters & 7))
         return fail(ctx, DR_ERR_INVALID_ARG, "workgroups must be 1 .. 2^20 and iters a multiple of 8 in 8 .. 2^24");
+    // the kernel cannot be pre-empted: keep a launch to tens of milliseconds of matrix work on a full device
+    if ((int64_t)workgroups * iters > (1ll << 26))
+        return fail(ctx, DR_ERR_INVALID_ARG, "workgroups * iters = %lld exceeds 2^26", (long long)workgroups * iters);
     DeviceGuard g(ctx->device);
     DR_HIP(ctx, launch_mfma_probe(shape, workgroups, iters, random_operands ? 1 : 0, sink, (hipStream_t)stream));
     if (flop) *flop = (double)workgroups * 4.0 * (double)iters * 8.0 * (shape == 32 ? 32768.0 : 16384.0);

@@ -102,6 +102,11 @@ bool attn_mfma_supported(const AttnArgs& a);
 hipError_t launch_attn_mfma_small(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_small_supported(const AttnArgs& a);
 
+// ---- evaluation aid: the proxy objective of the offline search (App. C, Eq. 22) ----------------------
+constexpr int kProxySlices = 64;     // partial sums per (b, h): partial is [B * H, kProxySlices, 2] doubles
+hipError_t launch_proxy_loss(const float* A_dense, const float* A_sparse, int BH, int N, const int64_t* nnz, int n_masks,
+                             int Sb, double target, double alpha, double* partial, double* out, hipStream_t s);
+
 // ---- measurement aid ---------------------------------------------------------------------
 // out[0] = shader-clock ticks, out[1] = 100 MHz ticks elapsed over a window of window_ticks (100 MHz units).
 hipError_t launch_clock_probe(unsigned long long window_ticks, unsigned long long* out, hipStream_t s);

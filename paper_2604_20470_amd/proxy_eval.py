@@ -4,13 +4,11 @@
 The attention *matrix* is not an output of the hot path, so it is read off the attention kernel column block by
 column block: with V set to the 128 one-hot columns of a key range, O = A V is that column range of A.  fp32 tensors
 keep the read-out exact to fp32 rounding (they run the fp32 attention kernel).  Meant for the small N of the proxy
-task (N x N floats are materialised); the Frobenius norms are taken on the host.
+task (N x N floats are materialised); the Frobenius norms and the penalty are reduced on the device by dr_proxy_loss.
 """
 from __future__ import annotations
 
 from typing import Tuple
-
-import numpy as np
 
 from . import binding as dr
 
@@ -62,10 +60,8 @@ def proxy_loss(ctx: dr.Context, Q, K, Nf: int, Hg: int, Wg: int, Bs: int, mode: 
     full_rp = (torch.arange(Sb + 1, dtype=torch.int32, device=Q.device) * Sb).view(1, 1, -1).repeat(B, 1, 1).contiguous()
     full_ci = torch.arange(Sb, dtype=torch.int32, device=Q.device).repeat(Sb).view(1, 1, -1).repeat(B, 1, 1).contiguous()
     A_dense = attention_matrix(ctx, shape, Q, K, full_rp, full_ci, 1, Sb * Sb)
-    ad = A_dense.double().cpu().numpy()
-    asp = A_sparse.double().cpu().numpy()
-    num = ((ad - asp) ** 2).sum(axis=(2, 3))
-    den = (ad ** 2).sum(axis=(2, 3))
-    nmse = float((num / den).mean())
-    sparsity = float(1.0 - nnz.double().mean().item() / float(Sb * Sb))
-    return nmse + alpha * max(0.0, target - sparsity), nmse, sparsity
+    assert A_dense.is_contiguous() and A_sparse.is_contiguous() and nnz.is_contiguous()
+    out = torch.empty(3, dtype=torch.float64, device=Q.device)
+    dr.dr_proxy_loss(ctx, A_dense, A_sparse, nnz, Sb, target, alpha, out)
+    loss, nmse, sparsity = out.tolist()
+    return loss, nmse, sparsity

@@ -10,8 +10,8 @@ import paper_2604_20470_amd as dr
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "dynamicrad.h")).read()
+def _declared(header="dynamicrad.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(dr_[a-z_]+)\s*\(", text)))
 
@@ -24,9 +24,19 @@ def test_header_declares_the_three_stage_calls():
 
 def test_library_exports_every_declared_symbol():
     lib = dr.load_library()
-    for n in _declared():
-        assert hasattr(lib, n), n
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        names = _declared(header)
+        assert names, header
+        for n in names:
+            assert hasattr(lib, n), (header, n)
     assert dr.version().startswith("dynamicrad-gfx950")
+
+
+def test_measurement_aids_are_not_in_the_product_header():
+    product, probes = _declared(), _declared("dynamicrad_probe.h")
+    assert probes == ["dr_clock_probe", "dr_mfma_probe"]
+    assert not set(product) & set(probes)
+    assert "dr_proxy_loss" in product
 
 
 def test_struct_layouts_match_header():

@@ -483,9 +483,13 @@ def test_maximum_frame_count_and_one_past_it():
         rowptr, colidx, nnz, cap = run.build_mask(scores, mode, par)
         assert_masks_equal(rowptr, colidx, nnz, o.build_mask(scores.cpu().numpy(), cls, mode, par, **kw))
     _attention_check(run, rowptr, colidx, cap, [(0, 0, None), (0, 1, None)], ATTN_TOL["f32"])
+    # one frame too many: every buffer has the size this shape would need (33 blocks per side), so that a moved limit
+    # shows up as a failed assertion and not as a launch on undersized buffers
     Q = torch.zeros((1, 1, 257 * 4, 64), device="cuda")
-    with pytest.raises(dr.DRError, match="UNSUPPORTED"):
-        dr.dr_block_scores(run.ctx, dr.shape_of(Q, 257, 2, 2, 32), Q, Q, 1, scores)
+    shape257 = dr.shape_of(Q, 257, 2, 2, 32)
+    scores257 = torch.zeros((1, 1, shape257.Sb, shape257.Sb), dtype=torch.float32, device="cuda")
+    with pytest.raises(dr.DRError, match="UNSUPPORTED.*256"):
+        dr.dr_block_scores(run.ctx, shape257, Q, Q, 1, scores257)
 
 
 def test_mfma_probe_runs_and_checks_its_arguments():
@@ -494,6 +498,7 @@ def test_mfma_probe_runs_and_checks_its_arguments():
     assert dr.dr_mfma_probe(ctx, 32, 8, 16, True, sink) == 8 * 4 * 16 * 8 * 32768.0
     assert dr.dr_mfma_probe(ctx, 16, 8, 16, False, sink) == 8 * 4 * 16 * 8 * 16384.0
     torch.cuda.synchronize()
-    for shape, wg, it in ((32, 0, 16), (32, 8, 0), (32, 8, 12), (8, 8, 16)):
+    # the last two: each argument within its own range, the product far beyond what one launch may hold the device for
+    for shape, wg, it in ((32, 0, 16), (32, 8, 0), (32, 8, 12), (8, 8, 16), (32, 1 << 20, 1 << 10), (16, 1 << 12, 1 << 24)):
         with pytest.raises(dr.DRError):
             dr.dr_mfma_probe(ctx, shape, wg, it, False, sink)

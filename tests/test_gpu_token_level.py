@@ -132,10 +132,28 @@ def test_limits_and_argument_errors():
     scores = _token_scores(run, 2)
     with pytest.raises(dr.DRError):
         _build(run, scores, float("nan"))
-    big = dr.Shape.from_buffer_copy(run.shape)
-    big.N, big.Nf = 8 * 64 * 40, 8 * 40                     # 20480 tokens: past the limit of the token-level order
-    dummy = torch.zeros(16, dtype=torch.float32, device="cuda")
-    with pytest.raises(dr.DRError):
-        dr.dr_token_scores(run.ctx, big, run.Q, run.K, 2, dummy)
-    with pytest.raises(dr.DRError):
-        dr.dr_build_mask_tokens(run.ctx, big, 0.0, 1.0, None, dummy, dummy, dummy, 16, dummy, None)
+    # Shapes that exceed exactly one limit of the token-level order, with every buffer at the size that shape would
+    # need: should a limit ever move, these calls compute on valid memory instead of reading past small stand-ins.
+    def buffers(B, H, N, d, Nf, Hg, Wg, Bs):
+        Q = torch.zeros((B, H, N, d), dtype=torch.float32, device="cuda")
+        shape = dr.shape_of(Q, Nf, Hg, Wg, Bs)
+        Sb = shape.Sb
+        scores = torch.zeros((B, 1, N, N), dtype=torch.float32, device="cuda")
+        rowptr = torch.zeros((B, 1, Sb + 1), dtype=torch.int32, device="cuda")
+        colidx = torch.zeros((B, 1, Sb * Sb), dtype=torch.int32, device="cuda")
+        nnz = torch.zeros((B, 1), dtype=torch.int64, device="cuda")
+        return Q, shape, scores, rowptr, colidx, nnz, Sb * Sb
+
+    # N = 80 frames x 16 x 16 = 20480 > 16384 tokens (frame count and tokens per frame within their limits)
+    Q, shape, scores, rowptr, colidx, nnz, cap = buffers(1, 2, 80 * 256, 64, 80, 16, 16, 64)
+    with pytest.raises(dr.DRError, match="16384"):
+        dr.dr_token_scores(run.ctx, shape, Q, Q, 2, scores)
+    with pytest.raises(dr.DRError, match="16384"):
+        dr.dr_build_mask_tokens(run.ctx, shape, 0.0, 1.0, None, scores, rowptr, colidx, cap, nnz, None)
+    del Q, scores, rowptr, colidx, nnz
+    # Nt = 72 x 64 = 4608 > 4096 tokens per frame at N = 9216 <= 16384: the scores are computed, the mask is refused
+    Q, shape, scores, rowptr, colidx, nnz, cap = buffers(1, 2, 2 * 4608, 64, 2, 72, 64, 64)
+    dr.dr_token_scores(run.ctx, shape, Q, Q, 2, scores)
+    with pytest.raises(dr.DRError, match="4096"):
+        dr.dr_build_mask_tokens(run.ctx, shape, 0.0, 1.0, None, scores, rowptr, colidx, cap, nnz, None)
+    torch.cuda.synchronize()
