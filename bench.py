@@ -50,7 +50,7 @@ def generate_on_device(wl, heads, device):
         for i, tensors in ex.map(one, range(len(heads))):
             for dst, src in zip(out, tensors):
                 dst[0, i].copy_(src)
-            if heads[i] < 2:
+            if heads[i] < 2 or heads[i] == heads[-1]:
                 host[heads[i]] = tensors
     return out, host
 
@@ -77,8 +77,9 @@ def read_traffic(kernel_tag):
         return None
 
 
-def cpu_baseline(wl, host_heads, ratio, kept_blocks_total, H, budget_s=15.0):
-    """Time the CPU oracle: scores + geometry + selection in full, attention on a sample of query blocks."""
+def cpu_baseline(wl, host_heads, mode, par, kept_blocks_total, H, O, rp_gpu, ci_gpu, budget_s=15.0):
+    """Times the CPU oracle (scores + geometry + selection in full, attention on a sample of query blocks) and compares
+    every attention row it computes with the output O of the launch that was timed.  Returns (cpu_baseline, parity)."""
     import numpy as np
     import torch
     from oracle import dynamicrad_oracle as o
@@ -89,32 +90,57 @@ def cpu_baseline(wl, host_heads, ratio, kept_blocks_total, H, budget_s=15.0):
     sc = o.block_scores(Q, K, wl.Bs, 2)
     tab = o.frame_table(wl.Nf, wl.Nt, wl.Bs, 1.0, wl.lam)
     cls = o.classify_blocks(wl.N, wl.Nt, wl.Bs, tab, 0.15, 0.60)
-    rp, ci = o.build_mask(sc.astype(np.float32), cls, "static", ratio)[0][0]
+    o.build_mask(sc.astype(np.float32), cls, mode, par)
     t_front = time.perf_counter() - t0
+    # the attention rows are taken under the mask the GPU emitted (the mask itself is compared bit for bit in the
+    # tests, where the oracle selects from the GPU's own fp32 scores)
+    rp, ci = rp_gpu.astype(np.int64), ci_gpu.astype(np.int64)
+    worst, checked = 0.0, 0
+
+    def check(hd_index, hd, qb, want):
+        nonlocal worst, checked
+        got = O[0, hd_index, qb * wl.Bs: qb * wl.Bs + want.shape[0]].to(torch.float64).cpu().numpy()
+        worst = max(worst, float(np.abs(got - want).max()))
+        checked += want.shape[0]
+
     rng = np.random.default_rng(7)
     done_blocks, rows, t_attn = 0, 0, 0.0
     for hd in (0, 1):
         Vh = f64(host_heads[hd][2])
         for qb in rng.permutation(wl.Sb):
             t1 = time.perf_counter()
-            o.masked_attention(Q[0, hd], K[0, hd], Vh, rp, ci, wl.Bs, rows=[int(qb)])
+            want = o.masked_attention(Q[0, hd], K[0, hd], Vh, rp, ci, wl.Bs, rows=[int(qb)])
             t_attn += time.perf_counter() - t1
+            check(hd, hd, int(qb), want[int(qb)])
             done_blocks += int(rp[qb + 1] - rp[qb])
             rows += 1
             if t_attn > budget_s:
                 break
         if t_attn > budget_s:
             break
+    # the last head sits at the far end of the launch's work-item order (the last XCD's run): first, last, and a few
+    # random query blocks of it (untimed)
+    last = max(host_heads)
+    if last >= 2:
+        Ql, Kl, Vl = (f64(t) for t in host_heads[last])
+        picks = sorted({0, wl.Sb - 1, wl.Sb - 2, *rng.integers(0, wl.Sb, 13).tolist()})
+        want = o.masked_attention(Ql, Kl, Vl, rp, ci, wl.Bs, rows=picks)
+        for qb in picks:
+            check(H - 1, last, qb, want[qb])
     est_ms = (t_front + t_attn * (kept_blocks_total * H / max(1, done_blocks))) * 1e3
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    return {"value": est_ms, "unit": "ms per attention call (extrapolated)", "cores": int(cores), "kind": "oracle",
+    tol = 2e-2 if wl.dtype == "bf16" else 1e-4
+    base = {"value": est_ms, "unit": "ms per attention call (extrapolated)", "cores": int(cores), "kind": "oracle",
             "sample": (f"block scores, geometry and selection in full ({t_front:.2f} s); fp64 masked attention on {rows} "
                        f"query-block rows of heads 0-1 ({done_blocks} kept key blocks, {t_attn:.2f} s) scaled by "
                        f"kept blocks x heads = {kept_blocks_total * H}")}
+    parity = {"rows": checked, "heads": sorted({0, 1, H - 1}), "max_abs_err": worst, "tol": tol,
+              "what": "output of the timed launch configuration against the fp64 oracle, element by element"}
+    return base, parity
 
 
 def main():
@@ -175,18 +201,7 @@ def main():
         if wl.ratio is not None:
             par = wl.ratio
         else:
-            cm = torch.empty((Sb, Sb), dtype=torch.uint8, device=dev)
-            dr.dr_class_map(ctx, shape, wl.lam, params, cm)
-            cmh = cm.cpu().numpy()
-            forced = int((cmh == 3).sum())
-            n_row = ((cmh == 1) | (cmh == 2)).sum(axis=1)
-            par = None
-            for i in range(1, 1001):
-                rho = i * 1e-3
-                kept = forced + int(np.maximum(1, np.floor(n_row * rho)).astype(np.int64)[n_row > 0].sum())
-                if 1.0 - kept / float(Sb * Sb) >= wl.target_sparsity:
-                    par = rho
-            assert par is not None, "target sparsity unreachable"
+            par, _ = dr.dr_static_ratio_for_sparsity(ctx, shape, wl.lam, params, wl.target_sparsity)
     else:
         mode, par = dr.MODE_DYNAMIC, wl.tau
 
@@ -212,6 +227,7 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     st = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evs])
     ms_scores, ms_mask, ms_attn = st.mean(axis=0).tolist()
+    st_median, st_min = np.median(st, axis=0).tolist(), st.min(axis=0).tolist()
 
     n_kept = int(nnz[0, 0].item())
     assert n_kept <= cap
@@ -228,12 +244,16 @@ def main():
                   "effective TFLOP/s of the attention kernel in roofline",
         "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{args.config}: B={wl.B} H={H} d={wl.d} Nf={wl.Nf} grid={wl.Hg}x{wl.Wg} N={wl.N} "
                                f"Bs={wl.Bs} {wl.mode} par={par:.3f} lambda={wl.lam} head_fuse={wl.head_fuse}",
                    "effective_sparsity": round(sparsity, 5), "kept_blocks": n_kept, "candidate_blocks": cap},
         "stages_ms": {"block_scores": round(ms_scores, 4), "build_mask": round(ms_mask, 4),
                       "sparse_attn_fwd": round(ms_attn, 4)},
+        "stages_ms_median": {"block_scores": round(st_median[0], 4), "build_mask": round(st_median[1], 4),
+                             "sparse_attn_fwd": round(st_median[2], 4)},
+        "stages_ms_min": {"block_scores": round(st_min[0], 4), "build_mask": round(st_min[1], 4),
+                          "sparse_attn_fwd": round(st_min[2], 4)},
         "effective_tflops": round(eff_tflops, 1),
         "dense_equivalent_tflops": round(dense_flop / (ms_attn * 1e-3) / 1e12, 1),
         "pct_bf16_mfma_peak": round(100.0 * eff_tflops / PEAK_BF16_TFLOPS, 2),
@@ -242,6 +262,8 @@ def main():
                                 if (wl.dtype == "bf16" and wl.d == 128) else "k_attn_generic"), "bound": "mfma", "achieved": round(eff_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(eff_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": read_traffic(f"k_attn_mfma_{args.config}") if wl.Bs == 128 else None,
+                     "traffic_source": (f"profiles/k_attn_mfma_{args.config}_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                        "runs of this command, scaled by a plain copy; not measured in this run"),
                      "flop_per_launch": flop, "avg_launch_ms": round(ms_attn, 4)},
     }
     # Shader clock while the attention kernel runs (separate, untimed pass): a one-wave probe on a side stream
@@ -329,11 +351,16 @@ def main():
         "uniform_sample": round(timed(lambda: dr.dr_build_mask(ctx, shape, dr.MODE_UNIFORM, 0.05, wl.lam, pz, None, rowptr, colidx, cap, nnz)), 4),
     }
     if not args.no_cpu_baseline:
-        log("[bench] timing the CPU oracle on a bounded sample ...")
-        result["cpu_baseline"] = cpu_baseline(wl, host_heads, par, n_kept, H)
+        log("[bench] timing the CPU oracle on a bounded sample and comparing it with the timed launch's output ...")
+        mode_name = "static" if mode == dr.MODE_STATIC else "dynamic"
+        result["cpu_baseline"], result["parity_in_bench"] = cpu_baseline(wl, host_heads, mode_name, par, n_kept, H, O, rp, ci)
     else:
-        result["cpu_baseline"] = None
+        result["cpu_baseline"], result["parity_in_bench"] = None, None
     print(json.dumps(result), flush=True)
+    pib = result.get("parity_in_bench")
+    if pib and not (pib["max_abs_err"] <= pib["tol"]):
+        log(f"[bench] PARITY FAILURE: max abs error {pib['max_abs_err']:.3e} above {pib['tol']:.0e}")
+        sys.exit(1)
 
 
 if __name__ == "__main__":

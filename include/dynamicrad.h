@@ -125,6 +125,22 @@ dr_status dr_mask_capacity(dr_ctx* ctx, const dr_shape* shape, double lambda, co
                            int64_t* candidate_blocks, int32_t* max_selectable_per_row);
 
 /*
+ * Static-ratio selection at a target effective sparsity.  Paper: k = max(1, floor(|P| rho)) of Eq. 8's keep rule;
+ * the kept count of a static-ratio row depends on the geometry only (FORCED blocks + max(1, floor(n rho)) of its
+ * n selectable blocks), so rho can be fixed before any score exists.  Returns the largest rho = i / 1000,
+ * i = 1 .. 1000, whose mask has effective sparsity 1 - kept / Sb^2 >= target (single-ratio rule; the product
+ * n * rho is taken in IEEE double).
+ *   target    in (0, 1)
+ *   ratio     host, receives rho
+ *   achieved  host, optional (may be NULL): the effective sparsity at that rho
+ * Synchronous (reads the per-row selectable counts of the cached geometry back to the host).
+ * Errors: DR_ERR_INVALID_ARG for NULL / out-of-range arguments; DR_ERR_UNSUPPORTED if no rho on the grid
+ * reaches the target (the never-pruned zone alone is too large).
+ */
+dr_status dr_static_ratio_for_sparsity(dr_ctx* ctx, const dr_shape* shape, double lambda, const dr_mask_params* params,
+                                       double target, double* ratio, double* achieved);
+
+/*
  * Stage (a).  Paper: proxy score, Eq. 9, with the fused-head mean of App. B, taken
  * at block granularity: score[b, m, qb, kb] = mean over heads of mask m of
  * mean_{p in qb}(Q_p) . mean_{q in kb}(K_q) / sqrt(d), means over valid tokens.
@@ -198,6 +214,13 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
  * bf16 inputs with d = 128 use bf16 MFMA (operands Q * log2(e)/sqrt(d) re-rounded to bf16, K,
  * V and the probabilities rounded to bf16) with fp32 accumulation and fp32 softmax, for every
  * block size; fp32 inputs, and bf16 inputs with d = 64, are computed in fp32 throughout.
+ * Accuracy range of the bf16 MFMA path: the second rounding of the scaled Q adds a logit error
+ * that grows with |logit|, so every group of 128 query rows that holds a row whose largest
+ * logit exceeds 44 in magnitude (64 in units of log2) is computed a second time, by a pass
+ * that feeds Q as stored and applies the scale in fp32; that pass overwrites O (and lse) of the
+ * group.  Both passes are launched by every call (the second one returns at once for groups
+ * that were not flagged); the flags live in context-owned device scratch (16 bytes per 128
+ * query rows and head), grown on demand: DR_ERR_NOMEM if that allocation fails.
  * Out-of-range key-block indices are clamped to [0, Sb) and row ranges are clipped to
  * [0, colidx_stride] (memory safety: a mask that overflowed its capacity is read as far as it
  * was written), neither is reported; a row

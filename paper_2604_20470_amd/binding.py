@@ -69,6 +69,7 @@ def load_library():
     lib.dr_last_error.restype = C.c_char_p
     lib.dr_class_map.argtypes = [vp, shp, f64, mpp, vp, vp]
     lib.dr_mask_capacity.argtypes = [vp, shp, f64, mpp, C.POINTER(i64), C.POINTER(i32)]
+    lib.dr_static_ratio_for_sparsity.argtypes = [vp, shp, f64, mpp, f64, C.POINTER(f64), C.POINTER(f64)]
     lib.dr_block_scores.argtypes = [vp, shp, vp, vp, i32, vp, vp]
     lib.dr_build_mask.argtypes = [vp, shp, i32, f64, f64, mpp, vp, vp, vp, i64, vp, vp]
     lib.dr_sparse_attn_fwd.argtypes = [vp, shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
@@ -77,7 +78,7 @@ def load_library():
     lib.dr_proxy_loss.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, i32, f64, f64, vp, vp]
     lib.dr_clock_probe.argtypes = [vp, C.c_uint64, vp, vp]
     lib.dr_mfma_probe.argtypes = [vp, i32, i32, i32, i32, vp, C.POINTER(f64), vp]
-    for name in ("dr_token_scores", "dr_build_mask_tokens", "dr_proxy_loss", "dr_clock_probe", "dr_mfma_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
+    for name in ("dr_token_scores", "dr_build_mask_tokens", "dr_proxy_loss", "dr_static_ratio_for_sparsity", "dr_clock_probe", "dr_mfma_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
                  "dr_sparse_attn_fwd"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -147,6 +148,15 @@ def dr_mask_capacity(ctx: Context, shape: Shape, lam: float, params: Optional[Ma
     cand, msel = C.c_int64(0), C.c_int32(0)
     ctx.check(ctx._lib.dr_mask_capacity(ctx._h, C.byref(shape), float(lam), _pp(params), C.byref(cand), C.byref(msel)))
     return cand.value, msel.value
+
+
+def dr_static_ratio_for_sparsity(ctx: Context, shape: Shape, lam: float, params: Optional[MaskParams],
+                                 target: float) -> Tuple[float, float]:
+    """(rho, achieved effective sparsity): the largest static ratio on a 1e-3 grid whose mask reaches `target`."""
+    rho, got = C.c_double(0.0), C.c_double(0.0)
+    ctx.check(ctx._lib.dr_static_ratio_for_sparsity(ctx._h, C.byref(shape), float(lam), _pp(params), float(target),
+                                                    C.byref(rho), C.byref(got)))
+    return rho.value, got.value
 
 
 def dr_block_scores(ctx: Context, shape: Shape, Q, K, head_fuse: int, scores, stream=None):

@@ -15,6 +15,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instructions
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
+    "-Wno-inline-asm",          # m0 is named as clobbered by the tile-load asm; clang warns that it is a reserved register
 ]
 
 
@@ -22,7 +23,7 @@ def build(verbose: bool = False, force: bool = True) -> str:
     """Compile every source and link the shared library.  Returns the library path."""
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    headers = [os.path.join(CSRC, "dr_internal.h"), os.path.join(HERE, "..", "include", "dynamicrad.h"),
+    headers = [os.path.join(CSRC, "dr_internal.h"), os.path.join(CSRC, "attn_mfma_common.h"), os.path.join(HERE, "..", "include", "dynamicrad.h"),
                os.path.join(HERE, "..", "include", "dynamicrad_probe.h")]
     hdr_time = max(os.path.getmtime(h) for h in headers)
 

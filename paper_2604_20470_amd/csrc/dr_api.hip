@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <vector>
 
 using namespace dr;
 
@@ -26,6 +27,9 @@ struct dr_ctx {
     int32_t* gcol = nullptr;
     int32_t* gcount = nullptr;
     size_t gcol_bytes = 0, gcount_bytes = 0;
+    // stage (c) scratch (bf16 MFMA paths): per-wave range flags of the fast pass, read by the fp32-scaled second pass
+    int32_t* attn_flags = nullptr;
+    size_t attn_flags_bytes = 0;
     // cached selection of the uniform rule (it depends on geometry, ratios and seed only): one mask of Sb rows
     uint32_t* uni_keep = nullptr;
     int32_t* uni_counts = nullptr;
@@ -238,7 +242,7 @@ void dr_destroy(dr_ctx* ctx) {
     {
         DeviceGuard g(ctx->device);
         void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->row_sel, ctx->totals, ctx->gcol,
-                        ctx->gcount, ctx->uni_keep, ctx->uni_counts, ctx->links, ctx->proxy_partial};
+                        ctx->gcount, ctx->attn_flags, ctx->uni_keep, ctx->uni_counts, ctx->links, ctx->proxy_partial};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
     }
@@ -275,6 +279,45 @@ dr_status dr_mask_capacity(dr_ctx* ctx, const dr_shape* shape, double lambda, co
     if ((st = ensure_geometry(ctx, shape, lambda, p, nullptr)) != DR_OK) return st;
     *candidate_blocks = ctx->cand_total;
     if (max_selectable_per_row) *max_selectable_per_row = ctx->max_sel;
+    return DR_OK;
+}
+
+dr_status dr_static_ratio_for_sparsity(dr_ctx* ctx, const dr_shape* shape, double lambda, const dr_mask_params* params,
+                                       double target, double* ratio, double* achieved) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    const dr_mask_params* p = params ? params : &kDefaults;
+    dr_status st;
+    if ((st = check_geometry(ctx, shape)) != DR_OK) return st;
+    if ((st = check_params(ctx, p, lambda)) != DR_OK) return st;
+    if (!ratio) return fail(ctx, DR_ERR_INVALID_ARG, "ratio is NULL");
+    if (!(target > 0.0 && target < 1.0)) return fail(ctx, DR_ERR_INVALID_ARG, "target must be in (0,1)");
+    DeviceGuard g(ctx->device);
+    if ((st = ensure_geometry(ctx, shape, lambda, p, nullptr)) != DR_OK) return st;
+    const int Sb = (shape->N + shape->Bs - 1) / shape->Bs;
+    std::vector<int32_t> n_row((size_t)Sb);
+    DR_HIP(ctx, hipMemcpy(n_row.data(), ctx->row_sel, (size_t)Sb * 4, hipMemcpyDeviceToHost));
+    int64_t selectable = 0;
+    for (int32_t n : n_row) selectable += n;
+    const int64_t forced = ctx->cand_total - selectable;
+    const double pairs = (double)Sb * (double)Sb;
+    bool found = false;
+    for (int i = 1; i <= 1000; ++i) {
+        const double rho = (double)i * 1e-3;
+        int64_t kept = forced;
+        for (int32_t n : n_row) {
+            if (n <= 0) continue;
+            const int64_t k = (int64_t)std::floor((double)n * rho);      // Eq. 8's keep rule
+            kept += k < 1 ? 1 : k;
+        }
+        const double sparsity = 1.0 - (double)kept / pairs;
+        if (sparsity >= target) {
+            *ratio = rho;
+            if (achieved) *achieved = sparsity;
+            found = true;
+        }
+    }
+    if (!found) return fail(ctx, DR_ERR_UNSUPPORTED, "no ratio reaches sparsity %.4f: the never-pruned zone alone keeps %lld of %.0f block pairs",
+                            target, (long long)forced, pairs);
     return DR_OK;
 }
 
@@ -464,6 +507,12 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
     a.Sb = (shape->N + shape->Bs - 1) / shape->Bs;
     a.bf16 = shape->dtype == DR_BF16;
     hipStream_t s = (hipStream_t)stream;
+    if (attn_mfma_supported(a) || attn_mfma_small_supported(a)) {
+        const size_t items = (size_t)shape->B * shape->H * ((size_t)(shape->N + 127) / 128);
+        dr_status fst;
+        if ((fst = grow(ctx, (void**)&ctx->attn_flags, &ctx->attn_flags_bytes, items * 4 * sizeof(int32_t))) != DR_OK) return fst;
+        a.flags = ctx->attn_flags;
+    }
     if (attn_mfma_supported(a)) {
         DR_HIP(ctx, launch_attn_mfma(a, s));
     } else if (attn_mfma_small_supported(a)) {

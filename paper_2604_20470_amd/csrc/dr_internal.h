@@ -92,6 +92,10 @@ struct AttnArgs {
     // scratch of the small-block MFMA path: per 128-row group the merged key-block list (laid out like colidx) and its length
     int32_t* gcol;               // [B, mask_heads, colidx_stride]
     int32_t* gcount;             // [B, mask_heads, ceil(N / 128)]
+    // scratch of the bf16 MFMA paths: one word per wave of a 128-query work item, non-zero when the fast pass found
+    // rows outside the accuracy range of its pre-scaled Q; those items are then taken again with fp32 scaling.
+    // NULL: no second pass.
+    int32_t* flags;              // [B * H * ceil(N / 128) * 4]
 };
 // Any d in {64,128}, Bs in {32,64,128}, f32 or bf16 storage; arithmetic in fp32 on the vector ALUs.
 hipError_t launch_attn_generic(const AttnArgs& a, hipStream_t s);

@@ -32,16 +32,13 @@
 // product multiplies): while it stays below 2^10 no probability exceeds 2^10; otherwise the row maximum
 // is formed, the reference is raised to it, the 64 output accumulators are rescaled and the chunk's
 // exponentials are redone.  The steady state therefore has no maximum reduction at all.
+#include "attn_mfma_common.h"
 #include "dr_internal.h"
 
 namespace dr {
 namespace {
 
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
-typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-typedef short v4s __attribute__((ext_vector_type(4)));
-typedef float v16f __attribute__((ext_vector_type(16)));
+using namespace mfma;
 
 constexpr int kD = 128, kBs = 128;
 constexpr int kWaves = 4, kThreads = kWaves * 64;
@@ -51,27 +48,6 @@ constexpr int kTileBytes = kChunkKeys * kRowBytes;   // 16 KB per operand per st
 constexpr int kStageBytes = 2 * kTileBytes;          // K then V
 constexpr int kLdsBytes = 2 * kStageBytes;           // two stages: 64 KB
 constexpr float kSumLimit = 1024.0f;                 // a lane's 32 probabilities of a chunk may sum to at most this
-
-// The barrier carries no memory fence on purpose: a fence would drain the prefetch of the next
-// chunk.  Ordering of the direct-to-LDS loads is enforced by the explicit vmcnt waits.
-#define DR_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
-#define DR_WAIT_VMCNT0() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
-
-// 16 bytes per lane from (base + voff) straight into LDS at m0_base + 16 * lane.  Issued through inline
-// assembly so that the compiler's wait-count insertion does not see an LDS write it cannot disambiguate
-// (it would drain the prefetch before every LDS read); completion is tracked by hand with vmcnt waits.
-__device__ __forceinline__ void dma16(uint32_t voff, uint64_t base, uint32_t m0_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(base), "s"(m0_base) : "memory");
-}
-__device__ __forceinline__ uint32_t lds_addr(const void* p) {
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-}
-__device__ __forceinline__ uint64_t uniform64(uint64_t x) {
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
 
 struct LoadPlan {
     uint32_t koff, voff;     // per-lane byte offset of this lane's 16 bytes within a 16-row group (swizzle folded in)
@@ -107,12 +83,6 @@ __device__ __forceinline__ void issue_chunk(const LoadPlan& lp, const char* Kh, 
     }
 }
 
-// max of a value with its copy in the lane 32 away (v_permlane32_swap: no LDS round trip)
-__device__ __forceinline__ float max_across_halves(float x) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-
 struct State {
     v16f o[4];        // O^T accumulators: channel block db, value j -> channel db*32 + (j/4)*8 + 4*half + j%4
     v16f cinit;       // -m_ref in all sixteen values: the C operand that starts every logit accumulation
@@ -125,7 +95,7 @@ struct ReadPlan {
     uint32_t v_addr[4];   // LDS address for channel block db (stage 0, mb 0, st 0, low half of the 8 keys)
 };
 
-template <int STAGE, class F>
+template <int STAGE, bool kExact, class F>
 __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[8], State& st, bool& first,
                                            int valid, int half, F&& issue) {
     typedef __attribute__((address_space(3))) const v8bf* lds_v8;
@@ -134,10 +104,17 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
 
     // ---- S^T = K Q^T : [64 keys x 32 queries], two independent accumulator chains ----
     // Q is pre-scaled by log2(e)/sqrt(d) and the accumulation starts from -m_ref, so the MFMA output is directly
-    // the exponent of 2: no per-element scale or subtract is left for the vector ALU.
+    // the exponent of 2: no per-element scale or subtract is left for the vector ALU.  (kExact: Q is taken as
+    // stored, the accumulation starts from zero and the scale and the reference are applied in fp32 afterwards.)
     v16f s[2];
-    s[0] = st.cinit;
-    s[1] = st.cinit;
+    if constexpr (kExact) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[0][j] = 0.f;
+        s[1] = s[0];
+    } else {
+        s[0] = st.cinit;
+        s[1] = st.cinit;
+    }
     {
         v8bf kf[2][8];
 #pragma unroll
@@ -151,6 +128,13 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][ks], qf[ks], s[mb], 0, 0, 0);
+    }
+    if constexpr (kExact) {
+        const float cs = kExpScale, neg_ref = -st.m_ref;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s[mb][j] = __builtin_fmaf(s[mb][j], cs, neg_ref);
     }
     __builtin_amdgcn_sched_barrier(0);
     // ---- V^T fragments: issued now so that they land while the softmax runs ----
@@ -245,6 +229,10 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
 // L2; id -> work item is remapped so that one XCD walks a contiguous run of (batch, head, query block) items:
 // the workgroups resident on an XCD at any time are then neighbouring query blocks of one head, whose kept key
 // blocks largely coincide (the forced zone of a frame), and their K/V tiles are served from that XCD's L2.
+// kExact = false: the fast pass over every item; each wave leaves in a.flags (when given) whether any of its rows
+// lies outside the accuracy range of the pre-scaled Q (see kExactLimit).  kExact = true: only the items flagged by
+// the fast pass, with the exponent scale applied in fp32.
+template <bool kExact>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma(AttnArgs a) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -254,6 +242,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int per_xcd = (total_items + kXcds - 1) / kXcds;
     const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     if (item >= total_items) return;
+    if constexpr (kExact) {
+        const int4 f = *reinterpret_cast<const int4*>(a.flags + (int64_t)item * 4);
+        if (__builtin_amdgcn_readfirstlane(f.x | f.y | f.z | f.w) == 0) return;
+    }
     const int qb = item % a.Sb, h = (item / a.Sb) % a.td.H, b = item / (a.Sb * a.td.H);
     const int N = a.td.N;
     const int64_t row_bytes = a.td.stride_n * 2;
@@ -269,7 +261,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int beg = min(max(__builtin_amdgcn_readfirstlane(rp[qb]), 0), lim);
     const int end = min(max(__builtin_amdgcn_readfirstlane(rp[qb + 1]), beg), lim);
 
-    const float cs = 1.4426950408889634f / sqrtf((float)kD);   // log2(e) / sqrt(d)
+    const float cs = kExact ? 1.0f : kExpScale;
     // Q^T fragments (B operand of S^T = K Q^T): lane holds query l32, channels ks*16 + 8*half .. +7
     const int q_wave0 = qb * kBs + wave * 32;
     v8bf qf[8];
@@ -343,13 +335,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int key0 = kb * kBs;
         const int n_chunks = (kb == a.Sb - 1) ? last_blk_chunks : 2;
         DR_BARRIER();
-        chunk_body<0>(rd, qf, st, first, N - key0, half, [&]() { if (n_chunks == 2) issue_chunk<1>(lp, Kh, Vh, key0 + kChunkKeys, N - 1); });
+        chunk_body<0, kExact>(rd, qf, st, first, N - key0, half, [&]() { if (n_chunks == 2) issue_chunk<1>(lp, Kh, Vh, key0 + kChunkKeys, N - 1); });
         DR_WAIT_VMCNT0();
         if (((blk + 1) & 63) == 0 && blk + 1 < n_blocks) win = load_window(blk + 1);
         kb_next = (blk + 1 < n_blocks) ? entry(win, blk + 1) : -1;
         if (n_chunks == 2) {
             DR_BARRIER();
-            chunk_body<1>(rd, qf, st, first, N - key0 - kChunkKeys, half, [&]() { if (kb_next >= 0) issue_chunk<0>(lp, Kh, Vh, kb_next * kBs, N - 1); });
+            chunk_body<1, kExact>(rd, qf, st, first, N - key0 - kChunkKeys, half, [&]() { if (kb_next >= 0) issue_chunk<0>(lp, Kh, Vh, kb_next * kBs, N - 1); });
             DR_WAIT_VMCNT0();
         } else if (kb_next >= 0) {   // only for a list that is not ascending: nothing was prefetched, load serially
             DR_BARRIER();
@@ -378,6 +370,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
             a.lse[((int64_t)b * a.td.H + h) * N + qrow] =
                 (l > 0.f) ? st.m_ref * 0.6931471805599453f + logf(l) : -INFINITY;
     }
+    if constexpr (!kExact) {
+        if (a.flags) {
+            const bool out_of_range = qrow < N && l > 0.f && !(fabsf(st.m_ref + __log2f(l)) <= kExactLimit);
+            const int any = __any(out_of_range) ? 1 : 0;
+            if (lane == 0) a.flags[(int64_t)item * 4 + wave] = any;
+        }
+    }
 }
 
 }  // namespace
@@ -389,12 +388,14 @@ bool attn_mfma_supported(const AttnArgs& a) {
 
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
     if (!attn_mfma_supported(a)) return hipErrorNotSupported;
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (attr != hipSuccess) return attr;
+    for (const void* k : {reinterpret_cast<const void*>(k_attn_mfma<false>), reinterpret_cast<const void*>(k_attn_mfma<true>)}) {
+        hipError_t attr = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (attr != hipSuccess) return attr;
+    }
     const int total = a.Sb * a.td.H * a.td.B;
     const int grid = (total + 7) / 8 * 8;          // every XCD gets the same number of slots
-    hipLaunchKernelGGL(k_attn_mfma, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    hipLaunchKernelGGL(k_attn_mfma<false>, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    if (a.flags) hipLaunchKernelGGL(k_attn_mfma<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
     return hipGetLastError();
 }
 

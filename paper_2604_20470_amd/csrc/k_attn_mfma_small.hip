@@ -15,6 +15,7 @@
 //   Bs = 32: a chunk is two consecutive entries of the union (keys 0..31 and 32..63 of the tile come from different
 //            places); every wavefront follows its own row and may use either half, both or none (a half it does
 //            not own is masked like keys past the end of the sequence).
+#include "attn_mfma_common.h"
 #include "dr_internal.h"
 
 #include <type_traits>
@@ -22,11 +23,7 @@
 namespace dr {
 namespace {
 
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
-typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-typedef short v4s __attribute__((ext_vector_type(4)));
-typedef float v16f __attribute__((ext_vector_type(16)));
+using namespace mfma;
 
 constexpr int kD = 128;
 constexpr int kRowsPerGroup = 128;                   // query rows per workgroup
@@ -38,27 +35,6 @@ constexpr int kStageBytes = 2 * kTileBytes;          // K then V
 constexpr int kLdsBytes = 2 * kStageBytes;
 constexpr float kSumLimit = 1024.0f;                 // a lane's probabilities of a chunk may sum to at most this
 constexpr int kNoBlock = 0x7fffffff;
-
-#define DR_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
-#define DR_WAIT_VMCNT0() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
-
-// direct-to-LDS 16-byte load, hand-tracked (see the Bs = 128 kernel for why it goes through inline assembly)
-__device__ __forceinline__ void dma16(uint32_t voff, uint64_t base, uint32_t m0_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(base), "s"(m0_base) : "memory");
-}
-__device__ __forceinline__ uint32_t lds_addr(const void* p) {
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-}
-__device__ __forceinline__ uint64_t uniform64(uint64_t x) {
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-__device__ __forceinline__ float max_across_halves(float x) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
 
 struct LoadPlan {
     uint32_t koff, voff;     // per-lane byte offset inside a 16-row group, swizzle folded in
@@ -126,7 +102,7 @@ struct ReadPlan {
 // One chunk for one wavefront.  MBM = 3: both 32-key halves of the tile are this wavefront's; MBM = 1: one half, the
 // one at byte offset sel_off of the K and V tiles (0 or 32 rows).  valid0 / valid1: number of real keys in the
 // (first / second) half processed (>= 32: all).
-template <int STAGE, int MBM, class F>
+template <int STAGE, int MBM, bool kExact, class F>
 __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[8], State& st, bool& first,
                                            int valid0, int valid1, float init0, float init1, uint32_t sel_off, int half,
                                            F&& issue) {
@@ -154,8 +130,10 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
     // init0 / init1: 0, or -inf for a half this wavefront does not own (its logits stay -inf, its probabilities 0).
     // The accumulation starts from -m_ref, so the matrix instruction delivers the logits relative to the exponent
     // reference (the accumulators have to be initialised anyway; the Bs = 128 kernel keeps this vector in registers).
+    // (kExact: Q is taken as stored, the accumulation starts from zero, and the exponent scale and the reference are
+    // applied in fp32 afterwards.)
     v16f s[2];
-    const float c0 = init0 - st.m_ref, c1 = init1 - st.m_ref;
+    const float c0 = kExact ? 0.f : init0 - st.m_ref, c1 = kExact ? 0.f : init1 - st.m_ref;
 #pragma unroll
     for (int j = 0; j < 16; ++j) { s[0][j] = c0; s[1][j] = c1; }
 #pragma unroll
@@ -177,6 +155,13 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
             for (int mb = MB0; mb < MB1; ++mb)
                 s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mb][k4], qf[batch * 4 + k4], s[mb], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (kExact) {
+        const float cs = kExpScale, a0 = init0 - st.m_ref, a1 = init1 - st.m_ref;
+#pragma unroll
+        for (int mb = MB0; mb < MB1; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s[mb][j] = __builtin_fmaf(s[mb][j], cs, mb ? a1 : a0);
     }
     v8bf vfa[2][4];
     read_v(MB0, vfa);                              // lands while the softmax runs
@@ -262,7 +247,9 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
 }
 
 // grid: (ceil(N / 128) * H * B) in one dimension, dealt to the XCDs as contiguous runs (see the Bs = 128 kernel).
-template <int BS>
+// kExact as in the Bs = 128 kernel: false = fast pass over every group, leaving per-wave range flags; true = the
+// flagged groups again with the exponent scale applied in fp32.
+template <int BS, bool kExact>
 __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
     constexpr int L = kRowsPerGroup / BS;          // CSR rows per workgroup: 2 or 4
     constexpr int kWavesPerRow = kWaves / L;       // 2 or 1
@@ -276,6 +263,10 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
     const int per_xcd = (total_items + kXcds - 1) / kXcds;
     const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     if (item >= total_items) return;
+    if constexpr (kExact) {
+        const int4 f = *reinterpret_cast<const int4*>(a.flags + (int64_t)item * 4);
+        if (__builtin_amdgcn_readfirstlane(f.x | f.y | f.z | f.w) == 0) return;
+    }
     const int qg = item % groups, h = (item / groups) % a.td.H, b = item / (groups * a.td.H);
     const int64_t row_bytes = a.td.stride_n * 2;
     const int64_t head_off = ((int64_t)b * a.td.stride_b + (int64_t)h * a.td.stride_h) * 2;
@@ -284,7 +275,7 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
     const char* Vh = reinterpret_cast<const char*>(a.V) + head_off;
     const int mh = (a.mask_heads == 1) ? 0 : h;
     const int32_t* rp = a.rowptr + ((int64_t)b * a.mask_heads + mh) * (a.Sb + 1);
-    const float cs = 1.4426950408889634f / sqrtf((float)kD);
+    const float cs = kExact ? 1.0f : kExpScale;
     const int q_wave0 = qg * kRowsPerGroup + wave * 32;
     v8bf qf[8];
     {
@@ -378,12 +369,12 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
         const int mbm = (int)((c.rows0 >> my_row) & 1u) | (int)(((c.rows1 >> my_row) & 1u) << 1);
         const int valid0 = N - c.kb0 * BS;
         if (BS == 64) {
-            if (mbm == 3) chunk_body<STAGE, 3>(rd, qf, st, first, valid0, valid0 - 32, 0.f, 0.f, 0u, half, issue);
+            if (mbm == 3) chunk_body<STAGE, 3, kExact>(rd, qf, st, first, valid0, valid0 - 32, 0.f, 0.f, 0u, half, issue);
             else issue();
         } else {
             const int valid1 = (c.kb1 >= 0) ? N - c.kb1 * BS : 32;
             if (mbm != 0)
-                chunk_body<STAGE, 3>(rd, qf, st, first, valid0, valid1, (mbm & 1) ? 0.f : -INFINITY,
+                chunk_body<STAGE, 3, kExact>(rd, qf, st, first, valid0, valid1, (mbm & 1) ? 0.f : -INFINITY,
                                      (mbm & 2) ? 0.f : -INFINITY, 0u, half, issue);
             else issue();
         }
@@ -430,6 +421,13 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
         if (a.lse && half == 0)
             a.lse[((int64_t)b * a.td.H + h) * N + qrow] =
                 (l > 0.f) ? st.m_ref * 0.6931471805599453f + logf(l) : -INFINITY;
+    }
+    if constexpr (!kExact) {
+        if (a.flags) {
+            const bool out_of_range = qrow < N && l > 0.f && !(fabsf(st.m_ref + __log2f(l)) <= kExactLimit);
+            const int any = __any(out_of_range) ? 1 : 0;
+            if (lane == 0) a.flags[(int64_t)item * 4 + wave] = any;
+        }
     }
 }
 
@@ -509,17 +507,21 @@ __global__ __launch_bounds__(256) void k_group_union(const int32_t* __restrict__
 // Both block sizes fit two workgroups per CU (256 registers per wave) without spilling into the loop; a spill reload
 // there would wait on the tile loads in flight.
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma_bs64(AttnArgs a) {
-    attn_small_body<64>(a);
+    attn_small_body<64, false>(a);
 }
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma_bs32(AttnArgs a) {
-    attn_small_body<32>(a);
+    attn_small_body<32, false>(a);
 }
+// the second pass over flagged groups: rare, so its register count (and occupancy) is left to the compiler
+__global__ __launch_bounds__(kThreads) void k_attn_mfma_bs64_exact(AttnArgs a) { attn_small_body<64, true>(a); }
+__global__ __launch_bounds__(kThreads) void k_attn_mfma_bs32_exact(AttnArgs a) { attn_small_body<32, true>(a); }
 
 template <class Kern>
-hipError_t launch_small(Kern kern, const AttnArgs& a, hipStream_t s) {
-    hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (attr != hipSuccess) return attr;
+hipError_t launch_small(Kern kern, Kern kern_exact, const AttnArgs& a, hipStream_t s) {
+    for (Kern k : {kern, kern_exact}) {
+        hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (attr != hipSuccess) return attr;
+    }
     const int groups = (a.td.N + kRowsPerGroup - 1) / kRowsPerGroup;
     {
         const int L = kRowsPerGroup / a.Bs;
@@ -537,6 +539,7 @@ hipError_t launch_small(Kern kern, const AttnArgs& a, hipStream_t s) {
     const int total = groups * a.td.H * a.td.B;
     const int grid = (total + 7) / 8 * 8;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    if (a.flags) hipLaunchKernelGGL(kern_exact, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
     return hipGetLastError();
 }
 
@@ -548,7 +551,8 @@ bool attn_mfma_small_supported(const AttnArgs& a) {
 
 hipError_t launch_attn_mfma_small(const AttnArgs& a, hipStream_t s) {
     if (!attn_mfma_small_supported(a)) return hipErrorNotSupported;
-    return a.Bs == 32 ? launch_small(k_attn_mfma_bs32, a, s) : launch_small(k_attn_mfma_bs64, a, s);
+    return a.Bs == 32 ? launch_small(k_attn_mfma_bs32, k_attn_mfma_bs32_exact, a, s)
+                      : launch_small(k_attn_mfma_bs64, k_attn_mfma_bs64_exact, a, s);
 }
 
 }  // namespace dr

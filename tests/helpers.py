@@ -8,6 +8,7 @@ import torch
 import paper_2604_20470_amd as dr
 from oracle import dynamicrad_oracle as o
 from workloads import Workload, make_qkv
+from workloads.generate import make_head, round_to_dtype
 
 DEFAULT = dict(gamma=1.0, theta_c=0.15, theta_m=0.60)
 
@@ -21,13 +22,31 @@ def oracle_class_map(wl: Workload, gamma=1.0, theta_c=0.15, theta_m=0.60, lam=No
     return o.classify_blocks(wl.N, wl.Nt, wl.Bs, tab, theta_c, theta_m)
 
 
+def make_qkv_threaded(wl: Workload, heads, workers: int = 12):
+    """make_qkv with the heads generated on host threads (bit-identical: every head has its own random stream)."""
+    from concurrent.futures import ThreadPoolExecutor
+    tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    out = [torch.empty((wl.B, len(heads), wl.N, wl.d), dtype=tdt) for _ in range(3)]
+
+    def one(job):
+        b, i = job
+        return b, i, [round_to_dtype(x, wl.dtype) for x in make_head(wl, b, heads[i])]
+
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        for b, i, tensors in ex.map(one, [(b, i) for b in range(wl.B) for i in range(len(heads))]):
+            for dst, src in zip(out, tensors):
+                dst[b, i].copy_(src)
+    return out
+
+
 class GpuRun:
     """Device tensors + library handles for one workload."""
 
-    def __init__(self, wl: Workload, heads=None, device="cuda:0", params: dr.MaskParams = None):
+    def __init__(self, wl: Workload, heads=None, device="cuda:0", params: dr.MaskParams = None, threads: int = 0):
         self.wl = wl
         self.heads = list(range(wl.H)) if heads is None else list(heads)
-        self.Qc, self.Kc, self.Vc = make_qkv(wl, self.heads)               # CPU, run dtype
+        gen = (lambda: make_qkv_threaded(wl, self.heads, threads)) if threads else (lambda: make_qkv(wl, self.heads))
+        self.Qc, self.Kc, self.Vc = gen()                                  # CPU, run dtype
         self.Q, self.K, self.V = (t.to(device) for t in (self.Qc, self.Kc, self.Vc))
         self.ctx = dr.Context(0)
         self.shape = dr.shape_of(self.Q, wl.Nf, wl.Hg, wl.Wg, wl.Bs)

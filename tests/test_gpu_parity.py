@@ -381,6 +381,43 @@ def test_exponent_reference_moves_and_survives_overflow(step, order):
     assert worst <= ATTN_TOL["bf16"], worst
 
 
+@pytest.mark.parametrize("bs", [128, 64, 32])
+@pytest.mark.parametrize("logit", [30.0, 60.0, 120.0])
+def test_large_logits_with_clustered_keys(logit, bs):
+    """Accuracy range of the bf16 MFMA paths.  They round Q * log2(e)/sqrt(d) to bf16 once more, a logit error that grows
+    with |logit| (about |s| * 2^-9, random in sign over the channels).  Ordinary Q values (nothing chosen to survive
+    that rounding), scaled so that the largest logits of a row sit near `logit`, against keys drawn around six centres,
+    so that each query sees hundreds of near-tied logits and the weights inside the winning cluster react to every
+    logit error.  The bar is the path's own: 2e-2.  (The header states the supported range.)"""
+    import dataclasses
+    wl = dataclasses.replace(tiny_case("ragged128"), Bs=bs)
+    run = GpuRun(wl)
+    N, d, H = wl.N, wl.d, wl.H
+    gen = torch.Generator().manual_seed(int(logit) * 7 + bs)
+    centres = torch.randn(H, 6, d, generator=gen)
+    member = torch.randint(0, 6, (H, N), generator=gen)
+    Kf = torch.gather(centres, 1, member[..., None].expand(H, N, d)) + 0.02 * torch.randn(H, N, d, generator=gen)
+    Qf = torch.randn(H, N, d, generator=gen) * (logit / 2.5)            # the best of six centres scores ~ 2.5 sigma
+    Vf = torch.randn(H, N, d, generator=gen)
+    run.Qc, run.Kc, run.Vc = (t[None].to(torch.bfloat16) for t in (Qf, Kf, Vf))
+    run.Q, run.K, run.V = run.Qc.cuda(), run.Kc.cuda(), run.Vc.cuda()
+    Sb = wl.Sb
+    rp, ci = o.full_csr(Sb)
+    rowptr = torch.from_numpy(rp.astype(np.int32)).view(1, 1, -1).contiguous().cuda()
+    colidx = torch.from_numpy(ci.astype(np.int32)).view(1, 1, -1).contiguous().cuda()
+    O = run.attention(rowptr, colidx, Sb * Sb)
+    worst, top = 0.0, 0.0
+    for h in range(H):
+        Qd, Kd, Vd = to_f64(run.Qc[0, h]), to_f64(run.Kc[0, h]), to_f64(run.Vc[0, h])
+        top = max(top, float(np.abs(Qd[:64] @ Kd.T).max() / np.sqrt(d)))
+        want = o.masked_attention(Qd, Kd, Vd, rp, ci, bs)
+        for qb, blk in want.items():
+            worst = max(worst, float(np.abs(to_f64(O[0, h, qb * bs: qb * bs + blk.shape[0]]) - blk).max()))
+    print(f"[clustered keys, Bs={bs}] largest |logit| ~ {top:.0f}: max-abs err {worst:.2e}", flush=True)
+    assert top >= 0.8 * logit
+    assert worst <= ATTN_TOL["bf16"], worst
+
+
 def test_clock_probe_reports_a_plausible_shader_clock():
     ctx = dr.Context(0)
     out = torch.zeros(2, dtype=torch.int64, device="cuda")

@@ -71,6 +71,31 @@ def test_config_pipeline(name, heads, n_heads_attn, n_rows):
     print(f"[{name}] attention max-abs err {worst:.3e} on {sample}", flush=True)
 
 
+def test_cfg4_with_all_heads_as_the_benchmark_launches_it():
+    """The launch bench.py times: all 40 heads of cfg4 in one call.  The work-item order of the attention kernel depends
+    on Sb * H (each XCD walks one contiguous eighth of the items), so a subset of heads takes a different mapping: here
+    the rows of the first head, of the head where the last XCD's run starts and of the last head are compared with the
+    oracle, the last rows of the last head among them."""
+    wl = CONFIGS["cfg4"]
+    rng = np.random.default_rng(4040)
+    run = GpuRun(wl, threads=12)
+    assert len(run.heads) == 40
+    cls = oracle_class_map(wl)
+    scores = run.block_scores()
+    par, achieved = dr.dr_static_ratio_for_sparsity(run.ctx, run.shape, wl.lam, run.params, wl.target_sparsity)
+    assert par == o.ratio_for_target_sparsity(cls, wl.target_sparsity)          # the ratio bench.py derives
+    rowptr, colidx, nnz, cap = run.build_mask(scores, "static", par)
+    masks = oracle_masks_from(scores, cls, "static", par)
+    assert_masks_equal(rowptr, colidx, nnz, masks)
+    assert abs(achieved - o.effective_sparsity(masks[0][0][0], wl.Sb)) < 1e-12
+    Sb = wl.Sb
+    sample = [(0, 0, [0, 1, Sb - 1]),
+              (0, 35, [0, 1] + rng.integers(0, Sb, 2).tolist()),                  # 7/8 of the items: the last XCD's first
+              (0, 39, sorted({Sb - 1, Sb - 2, Sb - 3, *rng.integers(0, Sb, 3).tolist()}))]
+    worst = _attention_check(run, rowptr, colidx, cap, sample, ATTN_TOL[wl.dtype])
+    print(f"[cfg4 x 40 heads] attention max-abs err {worst:.3e}", flush=True)
+
+
 @pytest.mark.parametrize("name", ["cfg2", "cfg3"])
 def test_per_head_masks_full(name):
     """head_fuse = 0: one mask per head, both modes, selection bit-exact on every head generated."""
