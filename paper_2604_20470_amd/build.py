@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdynamicrad.so")
-SOURCES = ["dr_api.hip", "k_scores.hip", "k_mask.hip", "k_attn_generic.hip", "k_attn_mfma.hip", "k_attn_mfma_small.hip", "k_tokens.hip", "k_proxy.hip", "k_clock_probe.hip"]
+SOURCES = ["dr_api.hip", "k_scores.hip", "k_mask.hip", "k_attn_generic.hip", "k_attn_mfma.hip", "k_attn_mfma_small.hip", "k_attn_mfma_pair.hip", "k_tokens.hip", "k_proxy.hip", "k_clock_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

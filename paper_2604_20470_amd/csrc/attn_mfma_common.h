@@ -13,6 +13,7 @@ typedef __bf16 v4bf __attribute__((ext_vector_type(4)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 // log2(e) / sqrt(128): the factor that turns a d = 128 dot product into an exponent of 2.
 constexpr float kExpScale = (float)(1.4426950408889634 / 11.313708498984760);

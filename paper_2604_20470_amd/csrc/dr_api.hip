@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -30,6 +31,7 @@ struct dr_ctx {
     // stage (c) scratch (bf16 MFMA paths): per-wave range flags of the fast pass, read by the fp32-scaled second pass
     int32_t* attn_flags = nullptr;
     size_t attn_flags_bytes = 0;
+    bool attn_pairs = true;      // block size 128: the kernel that walks pairs of query blocks (DR_ATTN_PAIRS=0 turns it off)
     // cached selection of the uniform rule (it depends on geometry, ratios and seed only): one mask of Sb rows
     uint32_t* uni_keep = nullptr;
     int32_t* uni_counts = nullptr;
@@ -233,6 +235,7 @@ dr_status dr_create(dr_ctx** out, int device) {
     if (!c) return DR_ERR_NOMEM;
     c->device = device;
     std::memset(&c->key, 0, sizeof c->key);
+    if (const char* e = std::getenv("DR_ATTN_PAIRS")) c->attn_pairs = !(e[0] == '0' && e[1] == 0);
     *out = c;
     return DR_OK;
 }
@@ -514,7 +517,25 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
         a.flags = ctx->attn_flags;
     }
     if (attn_mfma_supported(a)) {
-        DR_HIP(ctx, launch_attn_mfma(a, s));
+        // block size 128: pairs of adjacent query blocks walk the union of their two rows (scratch as for the small
+        // block sizes, one group = two rows); rows the pair kernel flags are taken again by the single-row kernel's
+        // second pass
+        const size_t n_pairs = ((size_t)a.Sb + 1) / 2;
+        bool pairs = ctx->attn_pairs && shape->N >= 64 && a.Sb < (1 << 28);
+        if (pairs) {
+            dr_status gst;
+            if ((gst = grow(ctx, (void**)&ctx->gcol, &ctx->gcol_bytes, (size_t)shape->B * mask_heads * (size_t)colidx_stride * 4 + 4)) != DR_OK) return gst;
+            if ((gst = grow(ctx, (void**)&ctx->gcount, &ctx->gcount_bytes, (size_t)shape->B * mask_heads * n_pairs * 4)) != DR_OK) return gst;
+            a.gcol = ctx->gcol;
+            a.gcount = ctx->gcount;
+            pairs = attn_mfma_pair_supported(a);
+        }
+        if (pairs) {
+            DR_HIP(ctx, launch_attn_mfma_pair(a, s));
+            DR_HIP(ctx, launch_attn_mfma_second_pass(a, s));
+        } else {
+            DR_HIP(ctx, launch_attn_mfma(a, s));
+        }
     } else if (attn_mfma_small_supported(a)) {
         if (a.Sb >= (1 << 28)) return fail(ctx, DR_ERR_UNSUPPORTED, "too many blocks for the packed group lists");
         const size_t groups = (size_t)(shape->N + 127) / 128;

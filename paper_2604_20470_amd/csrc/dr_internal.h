@@ -91,7 +91,7 @@ struct AttnArgs {
     int32_t bf16;
     // scratch of the small-block MFMA path: per 128-row group the merged key-block list (laid out like colidx) and its length
     int32_t* gcol;               // [B, mask_heads, colidx_stride]
-    int32_t* gcount;             // [B, mask_heads, ceil(N / 128)]
+    int32_t* gcount;             // [B, mask_heads, number of groups]
     // scratch of the bf16 MFMA paths: one word per wave of a 128-query work item, non-zero when the fast pass found
     // rows outside the accuracy range of its pre-scaled Q; those items are then taken again with fp32 scaling.
     // NULL: no second pass.
@@ -102,6 +102,15 @@ hipError_t launch_attn_generic(const AttnArgs& a, hipStream_t s);
 // bf16 storage, d = 128, Bs = 128: MFMA path.  Returns hipErrorNotSupported for other shapes.
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_supported(const AttnArgs& a);
+// The second pass of launch_attn_mfma alone: the items flagged in a.flags, with fp32 exponent scaling.
+hipError_t launch_attn_mfma_second_pass(const AttnArgs& a, hipStream_t s);
+// bf16 storage, d = 128, Bs = 128, N >= 64: MFMA path that walks pairs of adjacent query blocks (one wave per SIMD,
+// 64 queries per wave); needs gcol / gcount / flags.  Rows it flags must be taken again by the second pass above.
+hipError_t launch_attn_mfma_pair(const AttnArgs& a, hipStream_t s);
+bool attn_mfma_pair_supported(const AttnArgs& a);
+// Merged key-block lists of every group of L (2 or 4) consecutive CSR rows: a.gcol (laid out like colidx, a group's
+// entries at the colidx offset of its first row; entry = key block | rows-that-list-it << 28) and a.gcount.
+hipError_t launch_group_union(int L, const AttnArgs& a, hipStream_t s);
 // bf16 storage, d = 128, Bs = 32 or 64: MFMA path that walks the union of the CSR rows of a 128-query group.
 hipError_t launch_attn_mfma_small(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_small_supported(const AttnArgs& a);

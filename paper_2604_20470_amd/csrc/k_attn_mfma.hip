@@ -386,16 +386,32 @@ bool attn_mfma_supported(const AttnArgs& a) {
     return a.bf16 && a.td.d == kD && a.Bs == kBs && a.td.stride_n * 2 * kChunkKeys < (1ll << 31);
 }
 
-hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
-    if (!attn_mfma_supported(a)) return hipErrorNotSupported;
+static hipError_t allow_lds() {
     for (const void* k : {reinterpret_cast<const void*>(k_attn_mfma<false>), reinterpret_cast<const void*>(k_attn_mfma<true>)}) {
         hipError_t attr = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (attr != hipSuccess) return attr;
     }
+    return hipSuccess;
+}
+
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
+    if (!attn_mfma_supported(a)) return hipErrorNotSupported;
+    hipError_t attr = allow_lds();
+    if (attr != hipSuccess) return attr;
     const int total = a.Sb * a.td.H * a.td.B;
     const int grid = (total + 7) / 8 * 8;          // every XCD gets the same number of slots
     hipLaunchKernelGGL(k_attn_mfma<false>, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
     if (a.flags) hipLaunchKernelGGL(k_attn_mfma<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_mfma_second_pass(const AttnArgs& a, hipStream_t s) {
+    if (!attn_mfma_supported(a) || !a.flags) return hipErrorNotSupported;
+    hipError_t attr = allow_lds();
+    if (attr != hipSuccess) return attr;
+    const int total = a.Sb * a.td.H * a.td.B;
+    const int grid = (total + 7) / 8 * 8;
+    hipLaunchKernelGGL(k_attn_mfma<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
     return hipGetLastError();
 }
 

@@ -1,0 +1,588 @@
+// Stage (c), MFMA path for bf16, d = 128, Bs = 128 (paper Eqs. 12-13 with epsilon -> 0): the variant that walks
+// PAIRS of adjacent query blocks.  gfx950 (CDNA4) only.
+//
+// One workgroup = 4 wavefronts x 64 queries = query blocks 2p and 2p + 1 of one (batch, head); one wavefront per
+// SIMD, so that each may use the whole register file: the 128 O^T accumulators of its 64 queries live in the
+// accumulation registers, everything the vector ALU touches in the ordinary ones.  Compared with one query block
+// per workgroup (k_attn_mfma) every K / V fragment read from LDS feeds two matrix instructions instead of one, and
+// every K / V tile fetched from L2 serves 256 queries instead of 128: the kernel runs at the device's power limit,
+// so fewer joules per chunk is what buys time.
+// The workgroup walks the ascending UNION of the two CSR rows (formed beforehand by k_pair_union: key block in the
+// low 28 bits of an entry, the rows that list it in bits 28-29); a wavefront whose query block does not list a key
+// block runs the chunk with every logit masked.  Neighbouring query blocks share most of their key blocks (the
+// never-pruned zone of a frame, and, for score-based selection, similar pooled scores), so the union is only a few
+// per cent longer than a row.
+//
+// With a single wavefront per SIMD nothing else hides a wavefront's own latencies, so the chunk is software-pipelined
+// by hand: 64 matrix-instruction slots per chunk with one exponential, and at most a few other instructions, in the
+// shadow of each (see the schedule below); the exponentials of a chunk's last logit tile and its O += V P run under
+// the first slots of the next chunk.  v_dot2c_f32_bf16 is not used for the normaliser: it serialises with the matrix
+// pipe (a wavefront's matrix instruction + two exponentials + pack + dot takes 77 cycles, with two adds 49).
+// A lone wavefront also pays for every branch in full (a not-taken branch between two matrix instructions costs it
+// 9 to 26 cycles), so the 64 slots of a chunk are straight-line code without any masking: the pipelined loop takes
+// full 64-key chunks only, and the tile loads of the chunk after next are always issued (past the end of the list
+// they re-read the last window into the stage nobody reads).  The one chunk of a sequence that can be partial (in
+// its last key block) is taken before the loop, by plain code, from a 64-row window moved back to end at the last
+// row, whose leading rows are masked.  A wavefront whose query block does not list a chunk's key block skips the
+// chunk's arithmetic altogether (it only takes part in loads and barrier; the tile it has in flight waits).
+//
+// Softmax.  Q is pre-multiplied by log2(e)/sqrt(d) and every logit accumulation starts from -m_ref, so the first
+// product delivers the exponent of 2 directly.  The exponent reference m_ref of a query is the row maximum of its
+// first chunk and is never moved in this kernel (the accumulators are out of the vector ALU's reach): softmax is
+// invariant to the reference and fp32 / bf16 share one exponent range.  The first chunk of the union need not be
+// listed by the wavefront's own query block: its logits serve as a reference all the same.  Rows whose normaliser
+// leaves [2^-100, 2^100] (logits that far from the reference), or whose largest exponent is outside the accuracy
+// range of the pre-scaled Q (kExactLimit), are flagged and taken again by k_attn_mfma's second pass, which moves its
+// reference and scales in fp32.  The normaliser sums the exponentials before their rounding to bf16.
+#include "attn_mfma_common.h"
+#include "dr_internal.h"
+
+
+#include <type_traits>
+
+namespace dr {
+namespace {
+
+using namespace mfma;
+
+constexpr int kD = 128, kBs = 128;
+constexpr int kWaves = 4, kThreads = kWaves * 64;
+constexpr int kChunkKeys = 64;
+constexpr int kRowBytes = kD * 2;                    // 256
+constexpr int kTileBytes = kChunkKeys * kRowBytes;   // 16 KB per operand per stage
+constexpr int kStageBytes = 2 * kTileBytes;          // K then V
+constexpr int kLdsBytes = 2 * kStageBytes;           // two stages: 64 KB
+constexpr float kSumMax = 1.2676506e30f, kSumMin = 7.8886091e-31f;   // 2^100, 2^-100: outside, the row is flagged
+
+struct LoadPlan {
+    uint32_t koff_i[4], voff_i[4];   // per-lane byte offset of this lane's 16 bytes in the wave's four pieces of a chunk (swizzle folded in)
+    uint32_t m0_k;                   // LDS address of this wave's first K piece in stage 0
+};
+
+// Wave w moves pieces w, w+4, w+8, w+12 (1 KB = 4 rows each) of the K tile and of the V tile of the 64-row window at key0.
+template <int STAGE>
+__device__ __forceinline__ void issue_chunk(const LoadPlan& lp, const char* Kh, const char* Vh, int key0, int64_t row_bytes) {
+    const uint64_t kbase = uniform64((uint64_t)(Kh + (int64_t)key0 * row_bytes));
+    const uint64_t vbase = uniform64((uint64_t)(Vh + (int64_t)key0 * row_bytes));
+    const uint32_t m0 = lp.m0_k + STAGE * kStageBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        dma16(lp.koff_i[i], kbase, m0 + i * 4096);
+        dma16(lp.voff_i[i], vbase, m0 + kTileBytes + i * 4096);
+    }
+}
+
+struct State {
+    v16f o[2][4];     // [query half][channel block] O^T accumulators (accumulation registers)
+    v16f cinit[2];    // -m_ref of the lane's query column in each query half: C operand that starts a logit accumulation
+    float m_ref[2];
+    float l_part[2];
+    float lsum[2];    // per query half: the loop's share of the normaliser
+};
+
+struct ReadPlan {
+    uint32_t k_addr[8];   // LDS address for contraction step ks (stage 0, key sub-block 0)
+    uint32_t v_addr[4];   // LDS address for channel block db (stage 0, mb 0, st 0, low half of the 8 keys)
+};
+
+typedef __attribute__((address_space(3))) const v8bf* lds_v8;
+typedef __attribute__((address_space(3))) v4s* lds_v4;
+
+// O^T accumulators live in the accumulation registers: in the chunk loop only matrix instructions touch them.
+// The instruction goes through inline assembly so that its destination class can be chosen here (the compiler
+// picks one class for all its own matrix instructions); it therefore does not know this is a matrix instruction,
+// and the code that reads these accumulators with the vector ALU (epilogue) waits out the result latency by hand.
+__device__ __forceinline__ void mfma_pv(v16f& acc, const v8bf& a, const v8bf& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// The logit products go through inline assembly as well, so that the register classes are fixed here: logits in
+// ordinary registers (the exponentials read them), Q fragments in accumulation registers.  The schedule keeps every
+// reader of a logit tile at least one matrix-instruction slot behind the tile's last step.
+__device__ __forceinline__ void mfma_s_first(v16f& s, const v8bf& k, const v8bf& q, const v16f& c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(s) : "v"(k), "a"(q), "v"(c));
+}
+__device__ __forceinline__ void mfma_s(v16f& s, const v8bf& k, const v8bf& q) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(k), "a"(q));
+}
+// Normaliser: a row's sum of probabilities is taken from the bf16-rounded values, the ones O += V P multiplies, so
+// that numerator and denominator of the softmax see the same rounding (with one dominant key the quotient is then
+// exact; summing the unrounded exponentials leaves up to 2^-9 relative error in O and is 6 % faster).  A 4x4x4 matrix
+// instruction with an all-ones A operand can form the sum of a lane's four packed values in one issue slot, but
+// each one holds up the next 32x32x16 instruction by its two passes: no faster than the additions.
+__device__ __forceinline__ float rounded_sum(const v2bf& pk) { return (float)pk[0] + (float)pk[1]; }
+// The accumulators are operands of the wait so that every later read of them depends on it (a plain register copy
+// could otherwise be scheduled right behind the matrix instruction that produces its source).
+__device__ __forceinline__ void drain_mfma(v16f (&o)[2][4]) {
+    asm volatile("s_nop 15\n\ts_nop 15"
+                 : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[0][2]), "+a"(o[0][3]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[1][2]), "+a"(o[1][3])
+                 :: "memory");
+}
+#define DR_PIN_O() do { _Pragma("unroll") for (int qh_ = 0; qh_ < 2; ++qh_) _Pragma("unroll") for (int db_ = 0; db_ < 4; ++db_) asm volatile("" : "+a"(st.o[qh_][db_])); } while (0)
+
+// ---- schedule of one chunk: 64 matrix-instruction slots, one exponential per slot ----
+// A wave owns 64 queries = two query halves qh; a chunk has two 32-key halves mb; tile (mb, qh) is 32 keys x 32 queries.
+//   slots  0.. 7  S tile (0,0)                     16..23  S tile (0,1)       24..31  S tile (1,0)      40..47  S tile (1,1)
+//   slots  8..15  O += V P of tile (1,1) of the PREVIOUS chunk               32..39  O += V P (0,0)
+//   slots 48..55  O += V P (0,1)                                              56..63  O += V P (1,0)
+// The exponentials run one per slot behind the S tiles (stream position q = slot - 1: pair k = q / 2): tile (1,1) of the
+// previous chunk finishes in slots 0..8, (0,0) in 9..24, (0,1) in 25..40, (1,0) in 41..56, the first half of (1,1) in
+// 57..0.  A pair = two exponentials and one pack to bf16; one slot later the two packed values are unpacked again and
+// added to the normaliser.
+// LDS reads: K fragments of key half 1 in slots 10..17, V^T fragments of key half 0 in 18..25, of key half 1 in 44..51;
+// after that the chunk's LDS stage is not read again: the barrier sits before slot 56, and slots 56..63 also fetch the K
+// fragments of the next chunk's first key half and issue the tile loads of the chunk after it.
+constexpr int kBarrierSlot = 56;
+struct MfmaSlot { int kind, mb, qh, idx; };   // kind 0: S step idx of tile (mb, qh); 1: O += V P, idx = t * 4 + db
+constexpr MfmaSlot mfma_at(int slot) {
+    const int ph = slot >> 3, i = slot & 7;
+    switch (ph) {
+        case 0: return {0, 0, 0, i};
+        case 1: return {1, 1, 1, i};
+        case 2: return {0, 0, 1, i};
+        case 3: return {0, 1, 0, i};
+        case 4: return {1, 0, 0, i};
+        case 5: return {0, 1, 1, i};
+        case 6: return {1, 0, 1, i};
+        default: return {1, 1, 0, i};
+    }
+}
+struct ExpSlot { int mb, qh, gi, second; };   // exponential of value 2 gi + second of tile (mb, qh)
+constexpr ExpSlot exp_at(int slot) {
+    const int q = (slot + 63) & 63, k = q >> 1, second = q & 1;
+    if (k < 4) return {1, 1, 4 + k, second};
+    if (k < 12) return {0, 0, k - 4, second};
+    if (k < 20) return {0, 1, k - 12, second};
+    if (k < 28) return {1, 0, k - 20, second};
+    return {1, 1, k - 28, second};
+}
+
+struct Frags {
+    v8bf kf0[8], kf1[8];
+    v8bf vf[2][2][4];      // [mb][t][db]
+    v8bf pf[2][2][2];      // [mb][qh][t]
+    v16f s[2][2];          // [mb][qh]
+    float e_first[1];      // first exponential of the pair in flight
+};
+
+template <int I, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < E) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, E>(f);
+    }
+}
+
+// window rows below `lo` are not keys of this chunk for this wavefront (rows before a moved-back window's own keys, or
+// every row when the wavefront's query block does not list the key block): logit -inf
+__device__ __forceinline__ void mask_front(v16f& s, int mb, int half, int lo) {
+    int base = mb * 32 + half * 4;
+    asm volatile("" : "+v"(base));
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (base + (j >> 2) * 8 + (j & 3) < lo) s[j] = -INFINITY;
+}
+
+// Slots [FROM, TO) of the chunk whose tiles sit at LDS addresses rd (stage offset already added).  Slots 56..63 move rd
+// to the other stage, read the next chunk's first K fragments from there and issue one tile load each of the window at
+// kbase / vbase into the stage at m0_next; with kSkip they do only that (a wavefront that sits the chunk out).
+template <int FROM, int TO, bool kSkip>
+__device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v8bf (&qf)[2][8], State& st, Frags& fr,
+                                          const LoadPlan& lp, uint64_t kbase, uint64_t vbase, uint32_t m0_next) {
+    constexpr uint32_t kV = kTileBytes;
+    static_for<FROM, TO>([&](auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
+        constexpr MfmaSlot m = mfma_at(slot);
+        if constexpr (kSkip) {
+        } else if constexpr (m.kind == 0) {
+            if constexpr (m.idx == 0) mfma_s_first(fr.s[m.mb][m.qh], m.mb ? fr.kf1[0] : fr.kf0[0], qf[m.qh][0], st.cinit[m.qh]);
+            else mfma_s(fr.s[m.mb][m.qh], m.mb ? fr.kf1[m.idx] : fr.kf0[m.idx], qf[m.qh][m.idx]);
+        } else {
+            constexpr int t = m.idx >> 2, db = m.idx & 3;
+            mfma_pv(st.o[m.qh][db], fr.vf[m.mb][t][db], fr.pf[m.mb][m.qh][t]);
+        }
+        // ---- LDS reads ----
+        if constexpr (slot >= 10 && slot < 18) fr.kf1[slot - 10] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 10] + 32 * kRowBytes);
+        if constexpr ((slot >= 18 && slot < 26) || (slot >= 44 && slot < 52)) {
+            constexpr int mb = slot >= 44, f = mb ? slot - 44 : slot - 18, t = f >> 2, db = f & 3;
+            union { struct { v4s a, b; } s2; v8bf v; } u;
+            u.s2.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + kV + (mb * 32 + t * 16) * kRowBytes));
+            u.s2.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + kV + (mb * 32 + t * 16 + 8) * kRowBytes));
+            fr.vf[mb][t][db] = u.v;
+        }
+        if constexpr (slot >= 56 && TO == 64) {
+            // the chunk's own LDS stage is not read any more: the read addresses move to the other stage (stage_delta =
+            // +- one stage), then the next chunk's first K fragments are fetched (also when there is no next chunk: the
+            // address is a valid LDS address) and one tile load of the chunk after it is issued
+            rd.k_addr[slot - 56] += stage_delta;
+            if constexpr (slot < 60) rd.v_addr[slot - 56] += stage_delta;
+            fr.kf0[slot - 56] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 56]);
+            constexpr int i = (slot - 56) >> 1;
+            if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], kbase, m0_next + i * 4096);
+            else dma16(lp.voff_i[i], vbase, m0_next + kTileBytes + i * 4096);
+        }
+        // ---- one exponential; every second slot also the pack and the normaliser ----
+        if constexpr (!kSkip) {
+            constexpr ExpSlot e = exp_at(slot);
+            const float ev = __builtin_amdgcn_exp2f(fr.s[e.mb][e.qh][2 * e.gi + e.second]);
+            if constexpr (!e.second) {
+                fr.e_first[0] = ev;
+            } else {
+                constexpr int t = e.gi >> 2, i = (2 * e.gi) & 7;
+                v2bf pk;
+                pk[0] = (__bf16)fr.e_first[0];
+                pk[1] = (__bf16)ev;
+                asm volatile("" : "+v"(pk));      // anchors the pair in this slot of the interleaved stream
+                fr.pf[e.mb][e.qh][t][i] = pk[0];
+                fr.pf[e.mb][e.qh][t][i + 1] = pk[1];
+            }
+            if constexpr (!e.second) asm volatile("" : "+v"(fr.e_first[0]));
+            // the two probabilities packed in the previous slot go into the normaliser, as rounded
+            constexpr ExpSlot pe = exp_at((slot + 63) & 63);
+            if constexpr (pe.second) {
+                constexpr int t = pe.gi >> 2, i0 = (2 * pe.gi) & 7;
+                v2bf two;
+                two[0] = fr.pf[pe.mb][pe.qh][t][i0];
+                two[1] = fr.pf[pe.mb][pe.qh][t][i0 + 1];
+                st.lsum[pe.qh] += rounded_sum(two);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+}
+
+// Completes what the last chunk leaves in flight: the second half of its tile (1,1) (the pair whose first exponential
+// was taken in slot 63 included), then that tile's O += V P.
+__device__ __forceinline__ void finish_pending(State& st, Frags& fr, float (&lc)[2]) {
+    v2bf pk;
+    {
+        const float e1 = __builtin_amdgcn_exp2f(fr.s[1][1][7]);
+        pk[0] = (__bf16)fr.e_first[0];
+        pk[1] = (__bf16)e1;
+        // elements 4 .. 7 of the fragment: the first pair was packed in slot 62, this is the second
+        lc[1] += rounded_sum(pk);
+        fr.pf[1][1][0][6] = pk[0];
+        fr.pf[1][1][0][7] = pk[1];
+    }
+#pragma unroll
+    for (int gi = 4; gi < 8; ++gi) {
+        const float e0 = __builtin_amdgcn_exp2f(fr.s[1][1][2 * gi]);
+        const float e1 = __builtin_amdgcn_exp2f(fr.s[1][1][2 * gi + 1]);
+        pk[0] = (__bf16)e0;
+        pk[1] = (__bf16)e1;
+        lc[1] += rounded_sum(pk);
+        fr.pf[1][1][1][(2 * gi) & 7] = pk[0];
+        fr.pf[1][1][1][((2 * gi) & 7) + 1] = pk[1];
+    }
+#pragma unroll
+    for (int idx = 0; idx < 8; ++idx)
+        st.o[1][idx & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.vf[1][idx >> 2][idx & 3], fr.pf[1][1][idx >> 2], st.o[1][idx & 3], 0, 0, 0);
+}
+
+// One whole chunk by plain code (no pipelining), from the tiles at LDS addresses rd + stage_off: window rows below
+// `lo` masked.  Used before the pipelined loop for the sequence's partial chunk.
+__device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_off, const v8bf (&qf)[2][8], State& st,
+                                            float (&lc)[2], int lo, int half) {
+    constexpr uint32_t kV = kTileBytes;
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            v16f acc = st.cinit[qh];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const v8bf kf = *(lds_v8)(uintptr_t)(rd.k_addr[ks] + stage_off + mb * 32 * kRowBytes);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qh][ks], acc, 0, 0, 0);
+            }
+            mask_front(acc, mb, half, lo);
+            v8bf pf[2];
+#pragma unroll
+            for (int j = 0; j < 16; j += 2) {
+                v2bf pk;
+                pk[0] = (__bf16)__builtin_amdgcn_exp2f(acc[j]);
+                pk[1] = (__bf16)__builtin_amdgcn_exp2f(acc[j + 1]);
+                lc[qh] += rounded_sum(pk);
+                pf[j >> 3][j & 7] = pk[0];
+                pf[j >> 3][(j & 7) + 1] = pk[1];
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    union { struct { v4s a, b; } s2; v8bf v; } u;
+                    u.s2.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + stage_off + kV + (mb * 32 + t * 16) * kRowBytes));
+                    u.s2.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + stage_off + kV + (mb * 32 + t * 16 + 8) * kRowBytes));
+                    // (the compiler's own matrix instruction here: outside the hand-scheduled loop it looks after the
+                    // wait states between matrix instructions and their neighbours)
+                    st.o[qh][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[t], st.o[qh][db], 0, 0, 0);
+                }
+        }
+}
+
+// grid: (ceil(Sb / 2) * H * B) in one dimension, remapped so that one XCD walks a contiguous run of items.
+// One workgroup = 4 waves of 64 queries = two adjacent query blocks (waves 0-1: block 2p, waves 2-3: block 2p + 1).
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_pair(AttnArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    constexpr int kXcds = 8;
+    const int n_pairs = (a.Sb + 1) / 2;
+    const int total_items = n_pairs * a.td.H * a.td.B;
+    const int per_xcd = (total_items + kXcds - 1) / kXcds;
+    const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (item >= total_items) return;
+    const int pair = item % n_pairs, h = (item / n_pairs) % a.td.H, b = item / (n_pairs * a.td.H);
+    const int grp = wave >> 1;
+    const bool has_rows = 2 * pair + grp < a.Sb;
+    const int qb = min(2 * pair + grp, a.Sb - 1);
+    const int N = a.td.N;
+    const int64_t row_bytes = a.td.stride_n * 2;
+    const int64_t head_off = ((int64_t)b * a.td.stride_b + (int64_t)h * a.td.stride_h) * 2;
+    const char* Qh = reinterpret_cast<const char*>(a.Q) + head_off;
+    const char* Kh = reinterpret_cast<const char*>(a.K) + head_off;
+    const char* Vh = reinterpret_cast<const char*>(a.V) + head_off;
+    const int mh = (a.mask_heads == 1) ? 0 : h;
+    const int64_t mask_id = (int64_t)b * a.mask_heads + mh;
+    const int32_t* rp = a.rowptr + mask_id * (a.Sb + 1);
+    // the pair's merged list sits at the colidx offset of its first row (as k_group_union writes it)
+    const int64_t goff = min(max((int64_t)__builtin_amdgcn_readfirstlane(rp[2 * pair]), (int64_t)0), a.colidx_stride);
+    const int32_t* gl = a.gcol + mask_id * a.colidx_stride + goff;
+    const int cnt = __builtin_amdgcn_readfirstlane(a.gcount[mask_id * n_pairs + pair]);
+
+    const float cs = kExpScale;
+    const int q_wave0 = qb * kBs + (wave & 1) * 64;
+    v8bf qf[2][8];
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh) {
+        const int qrow = min(q_wave0 + qh * 32 + l32, N - 1);
+        const char* src = Qh + (int64_t)qrow * row_bytes + half * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const v8bf raw = *reinterpret_cast<const v8bf*>(src + ks * 32);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qf[qh][ks][i] = (__bf16)((float)raw[i] * cs);
+        }
+    }
+
+    const uint32_t lds0 = lds_addr(smem);
+    LoadPlan lp;
+    {
+        const int piece = lane & 15, r_first = wave * 4 + (lane >> 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            lp.koff_i[i] = (uint32_t)((r_first + 16 * i) * row_bytes) + ((piece ^ (r_first & 15)) << 4);
+            lp.voff_i[i] = (uint32_t)((r_first + 16 * i) * row_bytes) + ((piece ^ ((r_first & 3) << 2)) << 4);
+        }
+    }
+    lp.m0_k = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
+
+    ReadPlan rd;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) rd.k_addr[ks] = lds0 + l32 * kRowBytes + (((ks * 2 + half) ^ (l32 & 15)) << 4);
+    {
+        const int v_e = (lane & 15) >> 2, v_c = lane & 3, v_grp = (lane >> 4) & 1;
+        const int r0 = half * 4 + v_e;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const int piece = db * 4 + v_grp * 2 + (v_c >> 1);
+            rd.v_addr[db] = lds0 + r0 * kRowBytes + ((piece ^ (v_e << 2)) << 4) + (v_c & 1) * 8;
+        }
+    }
+
+    State st;
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh) {
+        st.m_ref[qh] = 0.f;
+        st.l_part[qh] = 0.f;
+        st.lsum[qh] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) st.cinit[qh][j] = 0.f;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) st.o[qh][db][j] = 0.f;
+    }
+    DR_PIN_O();
+
+    // ---- the chunk sequence.  Every entry of the merged list is a key block = two chunks of 64 keys, except the
+    // sequence's last key block, which holds n_last = N - (Sb - 1) * 128 keys: n_last / 64 full chunks for the loop
+    // and, if n_last is no multiple of 64, one partial chunk that is taken first, from the window of the sequence's
+    // last 64 rows (its leading 64 - n_last % 64 rows masked).  The list is ascending, so only its last entry can be
+    // that block. ----
+    const int n_last = N - (a.Sb - 1) * kBs;
+    const int part_keys = n_last % kChunkKeys;
+    int wbase = 0;
+    int win = (cnt > 0) ? gl[min(lane, cnt - 1)] : 0;
+    const uint32_t e_last = (cnt > 0) ? (uint32_t)gl[cnt - 1] : 0u;
+    // The Q fragments are only ever matrix-instruction operands: they live in accumulation registers, beside O, and
+    // leave the ordinary registers to what the vector ALU touches.  (The pin also marks them as arrived: the compiler,
+    // which cannot see the hand-issued tile loads, would otherwise re-wait for its own loads inside the loop.)
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(qf[qh][ks]));
+    asm volatile("" : "+v"(win));
+    const uint32_t e_last_s = __builtin_amdgcn_readfirstlane(e_last);
+    const bool has_last = cnt > 0 && (int)(e_last_s & 0x0fffffffu) >= a.Sb - 1;
+    const int n_chunks = 2 * cnt - (has_last ? 2 - n_last / kChunkKeys : 0);     // full chunks, in list order
+    const bool has_part = has_last && part_keys != 0;
+    const bool own_part = ((e_last_s >> (28 + grp)) & 1u) != 0;
+    struct Desc { int key0; bool own; };
+    auto describe = [&](int c) -> Desc {          // c < n_chunks, its entry inside the register window
+        const uint32_t e = (uint32_t)__builtin_amdgcn_readlane(win, (c >> 1) & 63);
+        const int kb = min((int)(e & 0x0fffffffu), a.Sb - 1);
+        // (the clamp never acts on a list as k_group_union writes it; it keeps any other list inside K / V)
+        return Desc{min(kb * kBs + (c & 1) * kChunkKeys, N - kChunkKeys), ((e >> (28 + grp)) & 1u) != 0};
+    };
+
+    if (n_chunks > 0 || has_part) {
+        // stage 0: the first full chunk (or, without one, the partial chunk); stage 1: the partial chunk
+        const Desc d0 = (n_chunks > 0) ? describe(0) : Desc{N - kChunkKeys, false};
+        issue_chunk<0>(lp, Kh, Vh, d0.key0, row_bytes);
+        if (has_part) issue_chunk<1>(lp, Kh, Vh, N - kChunkKeys, row_bytes);
+        DR_WAIT_VMCNT0();
+        DR_BARRIER();
+        // ---- exponent reference: the row maximum of the logits of stage 0, whether or not this wavefront's query
+        // block lists that key block ----
+        {
+            const int lo_ref = (n_chunks > 0) ? 0 : kChunkKeys - part_keys;
+#pragma unroll
+            for (int qh = 0; qh < 2; ++qh) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    v16f acc;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks) {
+                        const v8bf kf = *(lds_v8)(uintptr_t)(rd.k_addr[ks] + mb * 32 * kRowBytes);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qh][ks], acc, 0, 0, 0);
+                    }
+                    if (lo_ref > 0) mask_front(acc, mb, half, lo_ref);
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) mx = fmaxf(mx, acc[j]);
+                }
+                mx = max_across_halves(mx);          // finite: the chunk holds at least one key
+                st.m_ref[qh] = mx;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) st.cinit[qh][j] = -mx;
+            }
+        }
+        float lc[2] = {0.f, 0.f};
+        if (has_part) {
+            if (own_part) plain_chunk(rd, kStageBytes, qf, st, lc, kChunkKeys - part_keys, half);
+            DR_BARRIER();          // stage 1 is free again
+        }
+        if (n_chunks > 0) {
+            const Desc d1 = describe(min(1, n_chunks - 1));
+            issue_chunk<1>(lp, Kh, Vh, d1.key0, row_bytes);          // with a single chunk: that chunk again, never read
+            Frags fr;
+            // software-pipeline prologue: "previous chunk" = nothing (logits -inf, probabilities and V fragments 0)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) fr.s[1][1][j] = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) fr.pf[1][1][t][i] = (__bf16)0.f;
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) fr.vf[1][t][db][i] = (__bf16)0.f;
+            }
+            fr.e_first[0] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) fr.kf0[ks] = *(lds_v8)(uintptr_t)(rd.k_addr[ks]);
+            // Loop invariant at the top of a chunk: its tiles are complete in LDS for every wave, the K fragments of
+            // its first key half are on their way to registers, and the loads of the following chunk have been issued.
+            asm volatile("" : "+v"(st.cinit[0]), "+v"(st.cinit[1]), "+v"(fr.s[1][1]));
+            int stage = 0;                      // LDS stage of the chunk being consumed
+            bool own_cur = d0.own, own_nxt = d1.own;
+            for (int c = 0; c < n_chunks; ++c) {
+                DR_PIN_O();
+                // a wavefront that sits the chunk out leaves the tile it has in flight as it is: the next chunk it
+                // takes part in (or the code after the loop) completes it
+                if (own_cur) run_slots<0, kBarrierSlot, false>(rd, 0, qf, st, fr, lp, 0, 0, 0);
+                // the chunk after next (past the end of the list: the last chunk again, into the stage nobody reads)
+                const int c2 = min(c + 2, n_chunks - 1);
+                if ((c2 >> 1) >= wbase + 64) {
+                    wbase += 64;
+                    win = gl[min(wbase + lane, cnt - 1)];
+                    asm volatile("" : "+v"(win));
+                }
+                const Desc d2 = describe(c2);
+                const uint64_t kbase = uniform64((uint64_t)(Kh + (int64_t)d2.key0 * row_bytes));
+                const uint64_t vbase = uniform64((uint64_t)(Vh + (int64_t)d2.key0 * row_bytes));
+                DR_WAIT_VMCNT0();
+                DR_BARRIER();
+                __builtin_amdgcn_sched_barrier(0);
+                const uint32_t m0n = lp.m0_k + stage * kStageBytes;
+                if (own_cur) run_slots<kBarrierSlot, 64, false>(rd, stage ? -kStageBytes : kStageBytes, qf, st, fr, lp, kbase, vbase, m0n);
+                else run_slots<kBarrierSlot, 64, true>(rd, stage ? -kStageBytes : kStageBytes, qf, st, fr, lp, kbase, vbase, m0n);
+                DR_PIN_O();
+                own_cur = own_nxt;
+                own_nxt = d2.own;
+                stage ^= 1;
+            }
+            finish_pending(st, fr, lc);
+        }
+        st.l_part[0] = lc[0] + st.lsum[0];
+        st.l_part[1] = lc[1] + st.lsum[1];
+        DR_WAIT_VMCNT0();          // the loads issued by the last chunks write LDS: none may outlive the workgroup
+    }
+
+    // ---- epilogue ----
+    drain_mfma(st.o);
+    char* Oh = reinterpret_cast<char*>(a.O) + head_off;
+    bool out_of_range = false;
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh) {
+        const float l = st.l_part[qh] + __shfl_xor(st.l_part[qh], 32);
+        const float inv = (l > 0.f) ? 1.0f / l : 0.f;
+        const int qrow = q_wave0 + qh * 32 + l32;
+        if (has_rows && qrow < N) {
+            char* dst = Oh + (int64_t)qrow * row_bytes;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    v4bf v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = (__bf16)(st.o[qh][db][g * 4 + i] * inv);
+                    *reinterpret_cast<v4bf*>(dst + (db * 32 + g * 8 + half * 4) * 2) = v;
+                }
+            if (a.lse && half == 0)
+                a.lse[((int64_t)b * a.td.H + h) * N + qrow] =
+                    (l > 0.f) ? st.m_ref[qh] * 0.6931471805599453f + logf(l) : -INFINITY;
+            // a row that lists keys has l > 0 unless every exponential underflowed; l = 0 with an empty row is exact
+            const bool listed = rp[qb + 1] > rp[qb];
+            if (listed && !(l >= kSumMin && l <= kSumMax && fabsf(st.m_ref[qh] + __log2f(l)) <= kExactLimit)) out_of_range = true;
+        }
+    }
+    if (a.flags && has_rows) {      // two words per wave: it covers the rows of two 32-row waves of k_attn_mfma
+        const int any = __any(out_of_range) ? 1 : 0;
+        const int64_t base = (((int64_t)b * a.td.H + h) * a.Sb + qb) * 4 + (wave & 1) * 2;
+        if (lane < 2) a.flags[base + lane] = any;
+    }
+}
+
+}  // namespace
+
+bool attn_mfma_pair_supported(const AttnArgs& a) {
+    // every chunk is a full 64-row window: the sequence must hold one; the 32-bit per-lane offsets must cover it
+    return a.bf16 && a.td.d == kD && a.Bs == kBs && a.td.N >= kChunkKeys && a.Sb < (1 << 28) &&
+           a.td.stride_n * 2 * kChunkKeys < (1ll << 31) && a.gcol && a.gcount && a.flags;
+}
+
+hipError_t launch_attn_mfma_pair(const AttnArgs& a, hipStream_t s) {
+    if (!attn_mfma_pair_supported(a)) return hipErrorNotSupported;
+    hipError_t e = launch_group_union(2, a, s);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma_pair), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    const int total = ((a.Sb + 1) / 2) * a.td.H * a.td.B;
+    const int grid = (total + 7) / 8 * 8;          // every XCD gets the same number of slots
+    hipLaunchKernelGGL(k_attn_mfma_pair, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace dr

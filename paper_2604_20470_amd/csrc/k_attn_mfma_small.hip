@@ -431,16 +431,16 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
     }
 }
 
-// Pre-pass: the ascending union of the L = 128 / Bs CSR rows of every 128-row group, one entry per key block with the
+// Pre-pass: the ascending union of the L consecutive CSR rows of every group (L = 128 / Bs for the kernels of this
+// file, L = 2 for the kernel that walks pairs of 128-row query blocks), one entry per key block with the
 // set of rows that list it in the top four bits.  A group's entries are written at the colidx offset of its first row
 // (the union is never longer than the rows together), its length to gcount.  Indices are clamped to [0, Sb); an
 // index listed twice in a row counts once.
 // grid: (groups, mask_heads, B).  LDS: L * words presence bitmaps.
-template <int BS>
+template <int L>
 __global__ __launch_bounds__(256) void k_group_union(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
                                                      int64_t colidx_stride, int Sb, int groups,
                                                      int32_t* __restrict__ gcol, int32_t* __restrict__ gcount) {
-    constexpr int L = kRowsPerGroup / BS;
     extern __shared__ uint32_t pres[];                 // [L][words]
     __shared__ int s_wave[4];
     const int g = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
@@ -524,16 +524,7 @@ hipError_t launch_small(Kern kern, Kern kern_exact, const AttnArgs& a, hipStream
     }
     const int groups = (a.td.N + kRowsPerGroup - 1) / kRowsPerGroup;
     {
-        const int L = kRowsPerGroup / a.Bs;
-        const size_t lds = (size_t)L * ((a.Sb + 31) / 32) * 4;
-        const dim3 grid(groups, a.mask_heads, a.td.B);
-        if (a.Bs == 32)
-            hipLaunchKernelGGL(k_group_union<32>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups,
-                               a.gcol, a.gcount);
-        else
-            hipLaunchKernelGGL(k_group_union<64>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups,
-                               a.gcol, a.gcount);
-        hipError_t e = hipGetLastError();
+        hipError_t e = launch_group_union(kRowsPerGroup / a.Bs, a, s);
         if (e != hipSuccess) return e;
     }
     const int total = groups * a.td.H * a.td.B;
@@ -544,6 +535,18 @@ hipError_t launch_small(Kern kern, Kern kern_exact, const AttnArgs& a, hipStream
 }
 
 }  // namespace
+
+hipError_t launch_group_union(int L, const AttnArgs& a, hipStream_t s) {
+    if ((L != 2 && L != 4) || !a.gcol || !a.gcount) return hipErrorInvalidValue;
+    const int groups = (a.Sb + L - 1) / L;
+    const size_t lds = (size_t)L * ((a.Sb + 31) / 32) * 4;
+    const dim3 grid(groups, a.mask_heads, a.td.B);
+    if (L == 4)
+        hipLaunchKernelGGL(k_group_union<4>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);
+    else
+        hipLaunchKernelGGL(k_group_union<2>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);
+    return hipGetLastError();
+}
 
 bool attn_mfma_small_supported(const AttnArgs& a) {
     return a.bf16 && a.td.d == kD && (a.Bs == 32 || a.Bs == 64) && a.td.stride_n * 2 * kChunkKeys < (1ll << 31);
