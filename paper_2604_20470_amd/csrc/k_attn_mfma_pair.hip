@@ -220,12 +220,24 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
             if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], kbase, m0_next + i * 4096);
             else dma16(lp.voff_i[i], vbase, m0_next + kTileBytes + i * 4096);
         }
-        // ---- one exponential; every second slot also the pack and the normaliser ----
+        // ---- one exponential; every second slot also the pack; the two values packed in the previous slot go into
+        // the normaliser, as rounded (between the exponential and the pack that reads it: a transcendental's result
+        // is not ready for the very next instruction) ----
         if constexpr (!kSkip) {
             constexpr ExpSlot e = exp_at(slot);
             const float ev = __builtin_amdgcn_exp2f(fr.s[e.mb][e.qh][2 * e.gi + e.second]);
+            constexpr ExpSlot pe = exp_at((slot + 63) & 63);
+            if constexpr (pe.second) {
+                constexpr int t = pe.gi >> 2, i0 = (2 * pe.gi) & 7;
+                v2bf two;
+                two[0] = fr.pf[pe.mb][pe.qh][t][i0];
+                two[1] = fr.pf[pe.mb][pe.qh][t][i0 + 1];
+                st.lsum[pe.qh] += rounded_sum(two);
+                asm volatile("" : "+v"(st.lsum[pe.qh]));
+            }
             if constexpr (!e.second) {
                 fr.e_first[0] = ev;
+                asm volatile("" : "+v"(fr.e_first[0]));
             } else {
                 constexpr int t = e.gi >> 2, i = (2 * e.gi) & 7;
                 v2bf pk;
@@ -234,16 +246,6 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
                 asm volatile("" : "+v"(pk));      // anchors the pair in this slot of the interleaved stream
                 fr.pf[e.mb][e.qh][t][i] = pk[0];
                 fr.pf[e.mb][e.qh][t][i + 1] = pk[1];
-            }
-            if constexpr (!e.second) asm volatile("" : "+v"(fr.e_first[0]));
-            // the two probabilities packed in the previous slot go into the normaliser, as rounded
-            constexpr ExpSlot pe = exp_at((slot + 63) & 63);
-            if constexpr (pe.second) {
-                constexpr int t = pe.gi >> 2, i0 = (2 * pe.gi) & 7;
-                v2bf two;
-                two[0] = fr.pf[pe.mb][pe.qh][t][i0];
-                two[1] = fr.pf[pe.mb][pe.qh][t][i0 + 1];
-                st.lsum[pe.qh] += rounded_sum(two);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
