@@ -238,6 +238,26 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
                              int64_t colidx_stride, void* O, float* lse, void* stream);
 
 /*
+ * dr_sparse_attn_fwd for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results; the scratch the
+ * kernels need beyond their inputs and outputs (range flags of the bf16 MFMA paths; merged key-block lists and
+ * their lengths for block sizes 32 / 64 and for the block-size-128 kernel that walks pairs of query blocks) lies in
+ * a fixed 16 MiB area of device memory that is part of the library image (one copy per GPU, held until the process
+ * ends) instead of context-owned allocations.  The call allocates and frees nothing.
+ *   Needed: 16 bytes per 128 query rows and head, plus, on the list-walking paths, 4 bytes per entry of the colidx
+ *   arrays given (B * mask_heads * colidx_stride) and 4 bytes per group of rows.  A call that needs more than the
+ *   area holds is refused with DR_ERR_UNSUPPORTED (the message gives both figures); use dr_sparse_attn_fwd then.
+ * All calls on one GPU share the area, whatever their context: calls that overlap in time on one GPU race on it
+ * (calls queued on one stream do not overlap).  Nothing in it has to start at zero: every word a kernel reads was
+ * written earlier in the same call.
+ * Other errors as dr_sparse_attn_fwd.  DR_ERR_HIP if the area's address could not be resolved when the context
+ * was created.
+ */
+dr_status dr_sparse_attn_fwd_static(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, const void* V,
+                                    const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads,
+                                    int64_t colidx_stride, void* O, float* lse, void* stream);
+
+/*
  * Algorithm 1 in the paper's own order, for small sequences (an evaluation aid: it shows what the block-level
  * restatement of dr_build_mask changes).  Paper: proxy score of a token pair (Eq. 9), candidate set of a frame
  * pair (Eq. 7), score normalisation inside it (Eq. 10), decay-state thresholds with the keep-one safeguard

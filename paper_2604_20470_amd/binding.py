@@ -73,13 +73,14 @@ def load_library():
     lib.dr_block_scores.argtypes = [vp, shp, vp, vp, i32, vp, vp]
     lib.dr_build_mask.argtypes = [vp, shp, i32, f64, f64, mpp, vp, vp, vp, i64, vp, vp]
     lib.dr_sparse_attn_fwd.argtypes = [vp, shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
+    lib.dr_sparse_attn_fwd_static.argtypes = [vp, shp, vp, vp, vp, vp, vp, i32, i64, vp, vp, vp]
     lib.dr_token_scores.argtypes = [vp, shp, vp, vp, i32, vp, vp]
     lib.dr_build_mask_tokens.argtypes = [vp, shp, f64, f64, mpp, vp, vp, vp, i64, vp, vp, vp]
     lib.dr_proxy_loss.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, i32, f64, f64, vp, vp]
     lib.dr_clock_probe.argtypes = [vp, C.c_uint64, vp, vp]
     lib.dr_mfma_probe.argtypes = [vp, i32, i32, i32, i32, vp, C.POINTER(f64), vp]
     for name in ("dr_token_scores", "dr_build_mask_tokens", "dr_proxy_loss", "dr_static_ratio_for_sparsity", "dr_clock_probe", "dr_mfma_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
-                 "dr_sparse_attn_fwd"):
+                 "dr_sparse_attn_fwd", "dr_sparse_attn_fwd_static"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -176,6 +177,13 @@ def dr_sparse_attn_fwd(ctx: Context, shape: Shape, Q, K, V, rowptr, colidx, mask
     ctx.check(ctx._lib.dr_sparse_attn_fwd(ctx._h, C.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(rowptr),
                                           _ptr(colidx), int(mask_heads), int(colidx_stride), _ptr(O), _ptr(lse),
                                           _stream(stream)))
+
+
+def dr_sparse_attn_fwd_static(ctx: Context, shape: Shape, Q, K, V, rowptr, colidx, mask_heads: int, colidx_stride: int,
+                              O, lse=None, stream=None):
+    ctx.check(ctx._lib.dr_sparse_attn_fwd_static(ctx._h, C.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(rowptr),
+                                                 _ptr(colidx), int(mask_heads), int(colidx_stride), _ptr(O), _ptr(lse),
+                                                 _stream(stream)))
 
 
 def dr_token_scores(ctx: Context, shape: Shape, Q, K, head_fuse: int, scores, stream=None):

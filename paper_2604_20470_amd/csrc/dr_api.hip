@@ -14,8 +14,14 @@
 
 using namespace dr;
 
+// Scratch of dr_sparse_attn_fwd_static: one copy per GPU the library runs on, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress (dr_create resolves it, per device); kernels get the address.
+constexpr size_t kStaticScratchBytes = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 struct dr_ctx {
     int device = 0;
+    unsigned char* static_scratch = nullptr;   // device address of `scratch` on this context's device
     std::string err;
     // stage (a) scratch
     float* pooled = nullptr;
@@ -236,6 +242,15 @@ dr_status dr_create(dr_ctx** out, int device) {
     c->device = device;
     std::memset(&c->key, 0, sizeof c->key);
     if (const char* e = std::getenv("DR_ATTN_PAIRS")) c->attn_pairs = !(e[0] == '0' && e[1] == 0);
+    {
+        DeviceGuard g(device);
+        void* p = nullptr;
+        if (!g.ok || hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            delete c;
+            return DR_ERR_HIP;
+        }
+        c->static_scratch = static_cast<unsigned char*>(p);
+    }
     *out = c;
     return DR_OK;
 }
@@ -490,9 +505,29 @@ dr_status dr_build_mask_tokens(dr_ctx* ctx, const dr_shape* shape, double tau_ne
     return DR_OK;
 }
 
-dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, const void* V,
-                             const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads, int64_t colidx_stride,
-                             void* O, float* lse, void* stream) {
+namespace {
+
+// Scratch that the attention kernels need beyond their inputs and outputs, in bytes: the per-wave range flags of the
+// bf16 MFMA paths, and for the paths that walk merged key-block lists (block sizes 32 / 64, and the pair kernel of
+// block size 128) the lists and their lengths.  Zero for the fp32 arithmetic path.
+struct AttnScratchNeed { size_t flags, gcount, gcol; };
+
+AttnScratchNeed attn_scratch_need(const AttnArgs& a, bool pairs) {
+    AttnScratchNeed n{0, 0, 0};
+    if (!attn_mfma_supported(a) && !attn_mfma_small_supported(a)) return n;
+    const size_t groups128 = ((size_t)a.td.N + 127) / 128;
+    n.flags = (size_t)a.td.B * a.td.H * groups128 * 4 * sizeof(int32_t);
+    const bool lists = attn_mfma_small_supported(a) || pairs;
+    if (lists) {
+        const size_t groups = attn_mfma_small_supported(a) ? groups128 : ((size_t)a.Sb + 1) / 2;
+        n.gcount = (size_t)a.td.B * a.mask_heads * groups * sizeof(int32_t);
+        n.gcol = ((size_t)a.td.B * a.mask_heads * (size_t)a.colidx_stride + 1) * sizeof(int32_t);
+    }
+    return n;
+}
+
+dr_status attn_prepare(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, const void* V, const int32_t* rowptr,
+                       const int32_t* colidx, int32_t mask_heads, int64_t colidx_stride, void* O, float* lse, AttnArgs* out) {
     if (!ctx) return DR_ERR_INVALID_ARG;
     dr_status st;
     if ((st = check_tensor_shape(ctx, shape)) != DR_OK) return st;
@@ -501,7 +536,6 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
         return fail(ctx, DR_ERR_INVALID_ARG, "Q/K/V/O must be 16-byte aligned");
     if (mask_heads != 1 && mask_heads != shape->H) return fail(ctx, DR_ERR_INVALID_ARG, "mask_heads must be 1 or H");
     if (colidx_stride < 0) return fail(ctx, DR_ERR_INVALID_ARG, "negative colidx_stride");
-    DeviceGuard g(ctx->device);
     AttnArgs a{};
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
     a.rowptr = rowptr; a.colidx = colidx; a.colidx_stride = colidx_stride; a.mask_heads = mask_heads;
@@ -509,46 +543,74 @@ dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, 
     a.Bs = shape->Bs;
     a.Sb = (shape->N + shape->Bs - 1) / shape->Bs;
     a.bf16 = shape->dtype == DR_BF16;
-    hipStream_t s = (hipStream_t)stream;
-    if (attn_mfma_supported(a) || attn_mfma_small_supported(a)) {
-        const size_t items = (size_t)shape->B * shape->H * ((size_t)(shape->N + 127) / 128);
-        dr_status fst;
-        if ((fst = grow(ctx, (void**)&ctx->attn_flags, &ctx->attn_flags_bytes, items * 4 * sizeof(int32_t))) != DR_OK) return fst;
-        a.flags = ctx->attn_flags;
-    }
+    if (attn_mfma_small_supported(a) && a.Sb >= (1 << 28))
+        return fail(ctx, DR_ERR_UNSUPPORTED, "too many blocks for the packed group lists");
+    *out = a;
+    return DR_OK;
+}
+
+// Block size 128: pairs of adjacent query blocks walk the union of their two rows; rows the pair kernel flags are
+// taken again by the single-row kernel's second pass.
+bool attn_wants_pairs(const dr_ctx* ctx, const AttnArgs& a) {
+    return ctx->attn_pairs && attn_mfma_supported(a) && a.td.N >= 64 && a.Sb < (1 << 28);
+}
+
+dr_status attn_launch(dr_ctx* ctx, const AttnArgs& a, bool pairs, hipStream_t s) {
     if (attn_mfma_supported(a)) {
-        // block size 128: pairs of adjacent query blocks walk the union of their two rows (scratch as for the small
-        // block sizes, one group = two rows); rows the pair kernel flags are taken again by the single-row kernel's
-        // second pass
-        const size_t n_pairs = ((size_t)a.Sb + 1) / 2;
-        bool pairs = ctx->attn_pairs && shape->N >= 64 && a.Sb < (1 << 28);
-        if (pairs) {
-            dr_status gst;
-            if ((gst = grow(ctx, (void**)&ctx->gcol, &ctx->gcol_bytes, (size_t)shape->B * mask_heads * (size_t)colidx_stride * 4 + 4)) != DR_OK) return gst;
-            if ((gst = grow(ctx, (void**)&ctx->gcount, &ctx->gcount_bytes, (size_t)shape->B * mask_heads * n_pairs * 4)) != DR_OK) return gst;
-            a.gcol = ctx->gcol;
-            a.gcount = ctx->gcount;
-            pairs = attn_mfma_pair_supported(a);
-        }
-        if (pairs) {
+        if (pairs && attn_mfma_pair_supported(a)) {
             DR_HIP(ctx, launch_attn_mfma_pair(a, s));
             DR_HIP(ctx, launch_attn_mfma_second_pass(a, s));
         } else {
             DR_HIP(ctx, launch_attn_mfma(a, s));
         }
     } else if (attn_mfma_small_supported(a)) {
-        if (a.Sb >= (1 << 28)) return fail(ctx, DR_ERR_UNSUPPORTED, "too many blocks for the packed group lists");
-        const size_t groups = (size_t)(shape->N + 127) / 128;
-        dr_status gst;
-        if ((gst = grow(ctx, (void**)&ctx->gcol, &ctx->gcol_bytes, (size_t)shape->B * mask_heads * (size_t)colidx_stride * 4 + 4)) != DR_OK) return gst;
-        if ((gst = grow(ctx, (void**)&ctx->gcount, &ctx->gcount_bytes, (size_t)shape->B * mask_heads * groups * 4)) != DR_OK) return gst;
-        a.gcol = ctx->gcol;
-        a.gcount = ctx->gcount;
         DR_HIP(ctx, launch_attn_mfma_small(a, s));
     } else {
         DR_HIP(ctx, launch_attn_generic(a, s));
     }
     return DR_OK;
+}
+
+}  // namespace
+
+dr_status dr_sparse_attn_fwd(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, const void* V,
+                             const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads, int64_t colidx_stride,
+                             void* O, float* lse, void* stream) {
+    AttnArgs a{};
+    dr_status st;
+    if ((st = attn_prepare(ctx, shape, Q, K, V, rowptr, colidx, mask_heads, colidx_stride, O, lse, &a)) != DR_OK) return st;
+    DeviceGuard g(ctx->device);
+    const bool pairs = attn_wants_pairs(ctx, a);
+    const AttnScratchNeed need = attn_scratch_need(a, pairs);
+    if (need.flags && (st = grow(ctx, (void**)&ctx->attn_flags, &ctx->attn_flags_bytes, need.flags)) != DR_OK) return st;
+    if (need.gcol && (st = grow(ctx, (void**)&ctx->gcol, &ctx->gcol_bytes, need.gcol)) != DR_OK) return st;
+    if (need.gcount && (st = grow(ctx, (void**)&ctx->gcount, &ctx->gcount_bytes, need.gcount)) != DR_OK) return st;
+    a.flags = need.flags ? ctx->attn_flags : nullptr;
+    a.gcol = need.gcol ? ctx->gcol : nullptr;
+    a.gcount = need.gcount ? ctx->gcount : nullptr;
+    return attn_launch(ctx, a, pairs, (hipStream_t)stream);
+}
+
+dr_status dr_sparse_attn_fwd_static(dr_ctx* ctx, const dr_shape* shape, const void* Q, const void* K, const void* V,
+                                    const int32_t* rowptr, const int32_t* colidx, int32_t mask_heads, int64_t colidx_stride,
+                                    void* O, float* lse, void* stream) {
+    AttnArgs a{};
+    dr_status st;
+    if ((st = attn_prepare(ctx, shape, Q, K, V, rowptr, colidx, mask_heads, colidx_stride, O, lse, &a)) != DR_OK) return st;
+    if (!ctx->static_scratch) return fail(ctx, DR_ERR_HIP, "the static scratch area of this device was not resolved at dr_create");
+    DeviceGuard g(ctx->device);
+    const bool pairs = attn_wants_pairs(ctx, a);
+    const AttnScratchNeed need = attn_scratch_need(a, pairs);
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t total = up(need.flags) + up(need.gcount) + up(need.gcol);
+    if (total > kStaticScratchBytes)
+        return fail(ctx, DR_ERR_UNSUPPORTED, "this call needs %zu bytes of scratch (flags %zu, list lengths %zu, merged lists %zu); "
+                    "the static area holds %zu: use dr_sparse_attn_fwd", total, need.flags, need.gcount, need.gcol, kStaticScratchBytes);
+    unsigned char* base = ctx->static_scratch;
+    a.flags = need.flags ? reinterpret_cast<int32_t*>(base) : nullptr;
+    a.gcount = need.gcount ? reinterpret_cast<int32_t*>(base + up(need.flags)) : nullptr;
+    a.gcol = need.gcol ? reinterpret_cast<int32_t*>(base + up(need.flags) + up(need.gcount)) : nullptr;
+    return attn_launch(ctx, a, pairs, (hipStream_t)stream);
 }
 
 dr_status dr_proxy_loss(dr_ctx* ctx, const float* A_dense, const float* A_sparse, int32_t B, int32_t H, int32_t N,
