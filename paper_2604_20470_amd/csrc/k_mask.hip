@@ -382,11 +382,46 @@ __global__ __launch_bounds__(kThreads) void k_select_zscore(const uint8_t* __res
 }
 
 // grid: (Sb, masks, B)
-__global__ __launch_bounds__(kThreads) void k_emit(const uint32_t* __restrict__ keepbits,
-                                                   const int32_t* __restrict__ counts, int masks, int Sb, int shared,
-                                                   int32_t* __restrict__ rowptr, int32_t* __restrict__ colidx,
-                                                   int64_t capacity, int64_t* __restrict__ nnz) {
-    __shared__ long long s_off;
+// rowptr of every mask: the exclusive prefix of its rows' kept counts, one workgroup per mask (a row used to re-sum
+// all earlier counts itself: Sb^2 / 2 reads per mask).  grid: (masks, B).
+__global__ __launch_bounds__(kThreads) void k_row_offsets(const int32_t* __restrict__ counts, int masks, int Sb, int shared,
+                                                          int32_t* __restrict__ rowptr, int64_t* __restrict__ nnz) {
+    __shared__ long long s_wave[kWaves];
+    const int m = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int64_t mask_id = (int64_t)b * masks + m;
+    const int64_t src = shared ? 0 : mask_id * Sb;
+    int32_t* rp = rowptr + mask_id * (Sb + 1);
+    long long running = 0;
+    for (int base = 0; base < Sb; base += kThreads) {
+        const int i = base + tid;
+        const long long c = (i < Sb) ? counts[src + i] : 0;
+        long long incl = c;
+        for (int o = 1; o < 64; o <<= 1) {
+            const long long t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        long long wave_base = 0, total = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            if (w < wave) wave_base += s_wave[w];
+            total += s_wave[w];
+        }
+        if (i < Sb) rp[i] = (int32_t)(running + wave_base + incl - c);
+        running += total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        rp[Sb] = (int32_t)running;
+        nnz[mask_id] = running;
+    }
+}
+
+// One workgroup per row: the set bits of its keep bitmap, ascending, written from the row's offset on.
+__global__ __launch_bounds__(kThreads) void k_emit(const uint32_t* __restrict__ keepbits, int masks, int Sb, int shared,
+                                                   const int32_t* __restrict__ rowptr, int32_t* __restrict__ colidx,
+                                                   int64_t capacity) {
     __shared__ int s_wave[kWaves];
     const int qb = blockIdx.x, m = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -394,22 +429,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(const uint32_t* __restrict__ 
     const int64_t src = shared ? 0 : mask_id * Sb;      // shared: one selection (Sb rows) serves every (b, m)
     const int64_t row = src + qb;
     const int words = (Sb + 31) / 32;
-    if (tid == 0) s_off = 0;
-    __syncthreads();
-    long long part = 0;
-    for (int i = tid; i < qb; i += kThreads) part += counts[src + i];
-    for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off);
-    if (lane == 0 && part) atomicAdd((unsigned long long*)&s_off, (unsigned long long)part);
-    __syncthreads();
-    const long long off0 = s_off;
-    if (tid == 0) {
-        rowptr[mask_id * (Sb + 1) + qb] = (int32_t)off0;
-        if (qb == Sb - 1) {
-            const long long total = off0 + counts[row];
-            rowptr[mask_id * (Sb + 1) + Sb] = (int32_t)total;
-            nnz[mask_id] = total;
-        }
-    }
+    const long long off0 = rowptr[mask_id * (Sb + 1) + qb];      // negative only if the mask outgrew 32-bit offsets
     int32_t* out = colidx + mask_id * capacity;
     long long base = off0;
     for (int w0 = 0; w0 < words; w0 += kThreads) {
@@ -434,7 +454,7 @@ __global__ __launch_bounds__(kThreads) void k_emit(const uint32_t* __restrict__ 
         while (bits) {
             const int bit = __ffs(bits) - 1;
             bits &= bits - 1;
-            if (pos < capacity) out[pos] = wi * 32 + bit;
+            if (pos >= 0 && pos < capacity) out[pos] = wi * 32 + bit;
             ++pos;
         }
         base += total;
@@ -481,8 +501,9 @@ hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, i
 
 hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb, bool shared,
                        int32_t* rowptr, int32_t* colidx, int64_t capacity, int64_t* nnz, hipStream_t s) {
-    hipLaunchKernelGGL(k_emit, dim3(Sb, masks, B), dim3(kThreads), 0, s, keepbits, counts, masks, Sb, shared ? 1 : 0, rowptr, colidx,
-                       capacity, nnz);
+    hipLaunchKernelGGL(k_row_offsets, dim3(masks, B), dim3(kThreads), 0, s, counts, masks, Sb, shared ? 1 : 0, rowptr, nnz);
+    hipLaunchKernelGGL(k_emit, dim3(Sb, masks, B), dim3(kThreads), 0, s, keepbits, masks, Sb, shared ? 1 : 0, rowptr, colidx,
+                       capacity);
     return hipGetLastError();
 }
 
