@@ -218,8 +218,8 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
  * that grows with |logit|, so every group of 128 query rows that holds a row whose largest
  * logit exceeds 44 in magnitude (64 in units of log2) is computed a second time, by a pass
  * that feeds Q as stored and applies the scale in fp32; that pass overwrites O (and lse) of the
- * group.  Both passes are launched by every call (the second one returns at once for groups
- * that were not flagged); the flags live in context-owned device scratch (16 bytes per 128
+ * group.  Both passes are launched by every call (the second one only steps through the flags
+ * when no group was flagged); the flags live in context-owned device scratch (16 bytes per 128
  * query rows and head), grown on demand: DR_ERR_NOMEM if that allocation fails.
  * Out-of-range key-block indices are clamped to [0, Sb) and row ranges are clipped to
  * [0, colidx_stride] (memory safety: a mask that overflowed its capacity is read as far as it

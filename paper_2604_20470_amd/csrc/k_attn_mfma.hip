@@ -32,6 +32,8 @@
 // product multiplies): while it stays below 2^10 no probability exceeds 2^10; otherwise the row maximum
 // is formed, the reference is raised to it, the 64 output accumulators are rescaled and the chunk's
 // exponentials are redone.  The steady state therefore has no maximum reduction at all.
+#include <algorithm>
+
 #include "attn_mfma_common.h"
 #include "dr_internal.h"
 
@@ -225,27 +227,13 @@ __device__ __forceinline__ void chunk_body(const ReadPlan& rd, const v8bf (&qf)[
     __builtin_amdgcn_sched_barrier(0);   // keep the wait that follows below the last MFMA issue
 }
 
-// grid: (Sb * H * B) in one dimension.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own
-// L2; id -> work item is remapped so that one XCD walks a contiguous run of (batch, head, query block) items:
-// the workgroups resident on an XCD at any time are then neighbouring query blocks of one head, whose kept key
-// blocks largely coincide (the forced zone of a frame), and their K/V tiles are served from that XCD's L2.
-// kExact = false: the fast pass over every item; each wave leaves in a.flags (when given) whether any of its rows
-// lies outside the accuracy range of the pre-scaled Q (see kExactLimit).  kExact = true: only the items flagged by
-// the fast pass, with the exponent scale applied in fp32.
+// One work item = one query block of one (batch, head).  kExact = false: the fast pass; each wave leaves in a.flags
+// (when given) whether any of its rows lies outside the accuracy range of the pre-scaled Q (see kExactLimit).
+// kExact = true: the exponent scale applied in fp32 (the caller has checked that the item is flagged).
 template <bool kExact>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma(AttnArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+__device__ __forceinline__ void attn_item(const AttnArgs& a, int item, unsigned char* smem) {
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int half = lane >> 5, l32 = lane & 31;
-    constexpr int kXcds = 8;
-    const int total_items = a.Sb * a.td.H * a.td.B;
-    const int per_xcd = (total_items + kXcds - 1) / kXcds;
-    const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (item >= total_items) return;
-    if constexpr (kExact) {
-        const int4 f = *reinterpret_cast<const int4*>(a.flags + (int64_t)item * 4);
-        if (__builtin_amdgcn_readfirstlane(f.x | f.y | f.z | f.w) == 0) return;
-    }
     const int qb = item % a.Sb, h = (item / a.Sb) % a.td.H, b = item / (a.Sb * a.td.H);
     const int N = a.td.N;
     const int64_t row_bytes = a.td.stride_n * 2;
@@ -379,6 +367,34 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
 }
 
+// Fast pass.  grid: (Sb * H * B) in one dimension.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own
+// L2; id -> work item is remapped so that one XCD walks a contiguous run of (batch, head, query block) items:
+// the workgroups resident on an XCD at any time are then neighbouring query blocks of one head, whose kept key
+// blocks largely coincide (the forced zone of a frame), and their K/V tiles are served from that XCD's L2.
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma(AttnArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    constexpr int kXcds = 8;
+    const int total_items = a.Sb * a.td.H * a.td.B;
+    const int per_xcd = (total_items + kXcds - 1) / kXcds;
+    const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (item >= total_items) return;
+    attn_item<false>(a, item, smem);
+}
+
+// Second pass: the flagged items only.  Usually none is, so the grid is small and every workgroup steps through its
+// share of the flag words (a workgroup per item would spend 28 us at 23 640 items on starting workgroups that leave
+// at once).
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma_second_pass(AttnArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const int total_items = a.Sb * a.td.H * a.td.B;
+    for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
+        const int4 f = *reinterpret_cast<const int4*>(a.flags + (int64_t)item * 4);
+        if (__builtin_amdgcn_readfirstlane(f.x | f.y | f.z | f.w) == 0) continue;
+        attn_item<true>(a, item, smem);
+        __syncthreads();          // the next item's tile loads overwrite LDS that slower waves may still be reading
+    }
+}
+
 }  // namespace
 
 bool attn_mfma_supported(const AttnArgs& a) {
@@ -387,11 +403,16 @@ bool attn_mfma_supported(const AttnArgs& a) {
 }
 
 static hipError_t allow_lds() {
-    for (const void* k : {reinterpret_cast<const void*>(k_attn_mfma<false>), reinterpret_cast<const void*>(k_attn_mfma<true>)}) {
+    for (const void* k : {reinterpret_cast<const void*>(k_attn_mfma), reinterpret_cast<const void*>(k_attn_mfma_second_pass)}) {
         hipError_t attr = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (attr != hipSuccess) return attr;
     }
     return hipSuccess;
+}
+
+static void launch_second(const AttnArgs& a, hipStream_t s) {
+    const int total = a.Sb * a.td.H * a.td.B;
+    hipLaunchKernelGGL(k_attn_mfma_second_pass, dim3(std::min(total, 1024)), dim3(kThreads), kLdsBytes, s, a);
 }
 
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
@@ -400,8 +421,8 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
     if (attr != hipSuccess) return attr;
     const int total = a.Sb * a.td.H * a.td.B;
     const int grid = (total + 7) / 8 * 8;          // every XCD gets the same number of slots
-    hipLaunchKernelGGL(k_attn_mfma<false>, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
-    if (a.flags) hipLaunchKernelGGL(k_attn_mfma<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    hipLaunchKernelGGL(k_attn_mfma, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    if (a.flags) launch_second(a, s);
     return hipGetLastError();
 }
 
@@ -409,9 +430,7 @@ hipError_t launch_attn_mfma_second_pass(const AttnArgs& a, hipStream_t s) {
     if (!attn_mfma_supported(a) || !a.flags) return hipErrorNotSupported;
     hipError_t attr = allow_lds();
     if (attr != hipSuccess) return attr;
-    const int total = a.Sb * a.td.H * a.td.B;
-    const int grid = (total + 7) / 8 * 8;
-    hipLaunchKernelGGL(k_attn_mfma<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    launch_second(a, s);
     return hipGetLastError();
 }
 
