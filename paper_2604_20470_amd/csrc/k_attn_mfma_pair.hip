@@ -26,14 +26,14 @@
 // row, whose leading rows are masked.  A wavefront whose query block does not list a chunk's key block skips the
 // chunk's arithmetic altogether (it only takes part in loads and barrier; the tile it has in flight waits).
 //
-// Softmax.  Q is pre-multiplied by log2(e)/sqrt(d) and every logit accumulation starts from -m_ref, so the first
-// product delivers the exponent of 2 directly.  The exponent reference m_ref of a query is the row maximum of its
-// first chunk and is never moved in this kernel (the accumulators are out of the vector ALU's reach): softmax is
-// invariant to the reference and fp32 / bf16 share one exponent range.  The first chunk of the union need not be
-// listed by the wavefront's own query block: its logits serve as a reference all the same.  Rows whose normaliser
-// leaves [2^-100, 2^100] (logits that far from the reference), or whose largest exponent is outside the accuracy
-// range of the pre-scaled Q (kExactLimit), are flagged and taken again by k_attn_mfma's second pass, which moves its
-// reference and scales in fp32.  The normaliser sums the exponentials before their rounding to bf16.
+// Softmax.  Q is pre-multiplied by log2(e)/sqrt(d), so the logit products are exponents of 2, and they are
+// exponentiated as they are: no exponent reference is subtracted.  Softmax is invariant to a reference; one is only
+// needed to keep 2^x in range, and a row whose largest exponent exceeds kExactLimit = 64 in magnitude is outside
+// the accuracy range of the pre-scaled Q anyway: such rows (and any whose normaliser leaves [2^-100, 2^100]) are
+// flagged and taken again by k_attn_mfma's second pass, which moves a reference and scales in fp32.  Below the
+// limit nothing overflows (fp32 and bf16 share one exponent range, so large or small probabilities lose no
+// precision), the logit accumulation starts from the constant 0, and the accumulators, which are out of the vector
+// ALU's reach, never need rescaling.  The normaliser sums the probabilities as rounded to bf16.
 #include "attn_mfma_common.h"
 #include "dr_internal.h"
 
@@ -74,8 +74,6 @@ __device__ __forceinline__ void issue_chunk(const LoadPlan& lp, const char* Kh, 
 
 struct State {
     v16f o[2][4];     // [query half][channel block] O^T accumulators (accumulation registers)
-    v16f cinit[2];    // -m_ref of the lane's query column in each query half: C operand that starts a logit accumulation
-    float m_ref[2];
     float l_part[2];
     float lsum[2];    // per query half: the loop's share of the normaliser
 };
@@ -98,8 +96,8 @@ __device__ __forceinline__ void mfma_pv(v16f& acc, const v8bf& a, const v8bf& b)
 // The logit products go through inline assembly as well, so that the register classes are fixed here: logits in
 // ordinary registers (the exponentials read them), Q fragments in accumulation registers.  The schedule keeps every
 // reader of a logit tile at least one matrix-instruction slot behind the tile's last step.
-__device__ __forceinline__ void mfma_s_first(v16f& s, const v8bf& k, const v8bf& q, const v16f& c) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(s) : "v"(k), "a"(q), "v"(c));
+__device__ __forceinline__ void mfma_s_first(v16f& s, const v8bf& k, const v8bf& q) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(k), "a"(q));
 }
 __device__ __forceinline__ void mfma_s(v16f& s, const v8bf& k, const v8bf& q) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(k), "a"(q));
@@ -194,7 +192,7 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
         constexpr MfmaSlot m = mfma_at(slot);
         if constexpr (kSkip) {
         } else if constexpr (m.kind == 0) {
-            if constexpr (m.idx == 0) mfma_s_first(fr.s[m.mb][m.qh], m.mb ? fr.kf1[0] : fr.kf0[0], qf[m.qh][0], st.cinit[m.qh]);
+            if constexpr (m.idx == 0) mfma_s_first(fr.s[m.mb][m.qh], m.mb ? fr.kf1[0] : fr.kf0[0], qf[m.qh][0]);
             else mfma_s(fr.s[m.mb][m.qh], m.mb ? fr.kf1[m.idx] : fr.kf0[m.idx], qf[m.qh][m.idx]);
         } else {
             constexpr int t = m.idx >> 2, db = m.idx & 3;
@@ -289,7 +287,9 @@ __device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_o
     for (int qh = 0; qh < 2; ++qh)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
-            v16f acc = st.cinit[qh];
+            v16f acc;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[j] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 const v8bf kf = *(lds_v8)(uintptr_t)(rd.k_addr[ks] + stage_off + mb * 32 * kRowBytes);
@@ -393,11 +393,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     State st;
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
-        st.m_ref[qh] = 0.f;
         st.l_part[qh] = 0.f;
         st.lsum[qh] = 0.f;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) st.cinit[qh][j] = 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -443,33 +440,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         if (has_part) issue_chunk<1>(lp, Kh, Vh, N - kChunkKeys, row_bytes);
         DR_WAIT_VMCNT0();
         DR_BARRIER();
-        // ---- exponent reference: the row maximum of the logits of stage 0, whether or not this wavefront's query
-        // block lists that key block ----
-        {
-            const int lo_ref = (n_chunks > 0) ? 0 : kChunkKeys - part_keys;
-#pragma unroll
-            for (int qh = 0; qh < 2; ++qh) {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb) {
-                    v16f acc;
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-#pragma unroll
-                    for (int ks = 0; ks < 8; ++ks) {
-                        const v8bf kf = *(lds_v8)(uintptr_t)(rd.k_addr[ks] + mb * 32 * kRowBytes);
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qh][ks], acc, 0, 0, 0);
-                    }
-                    if (lo_ref > 0) mask_front(acc, mb, half, lo_ref);
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) mx = fmaxf(mx, acc[j]);
-                }
-                mx = max_across_halves(mx);          // finite: the chunk holds at least one key
-                st.m_ref[qh] = mx;
-#pragma unroll
-                for (int j = 0; j < 16; ++j) st.cinit[qh][j] = -mx;
-            }
-        }
         float lc[2] = {0.f, 0.f};
         if (has_part) {
             if (own_part) plain_chunk(rd, kStageBytes, qf, st, lc, kChunkKeys - part_keys, half);
@@ -496,7 +466,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             for (int ks = 0; ks < 8; ++ks) fr.kf0[ks] = *(lds_v8)(uintptr_t)(rd.k_addr[ks]);
             // Loop invariant at the top of a chunk: its tiles are complete in LDS for every wave, the K fragments of
             // its first key half are on their way to registers, and the loads of the following chunk have been issued.
-            asm volatile("" : "+v"(st.cinit[0]), "+v"(st.cinit[1]), "+v"(fr.s[1][1]));
+            asm volatile("" : "+v"(fr.s[1][1]));
             int stage = 0;                      // LDS stage of the chunk being consumed
             bool own_cur = d0.own, own_nxt = d1.own;
             for (int c = 0; c < n_chunks; ++c) {
@@ -554,10 +524,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                 }
             if (a.lse && half == 0)
                 a.lse[((int64_t)b * a.td.H + h) * N + qrow] =
-                    (l > 0.f) ? st.m_ref[qh] * 0.6931471805599453f + logf(l) : -INFINITY;
+                    (l > 0.f) ? logf(l) : -INFINITY;
             // a row that lists keys has l > 0 unless every exponential underflowed; l = 0 with an empty row is exact
             const bool listed = rp[qb + 1] > rp[qb];
-            if (listed && !(l >= kSumMin && l <= kSumMax && fabsf(st.m_ref[qh] + __log2f(l)) <= kExactLimit)) out_of_range = true;
+            if (listed && !(l >= kSumMin && l <= kSumMax && fabsf(__log2f(l)) <= kExactLimit)) out_of_range = true;
         }
     }
     if (a.flags && has_rows) {      // two words per wave: it covers the rows of two 32-row waves of k_attn_mfma
