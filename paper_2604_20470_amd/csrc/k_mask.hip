@@ -274,6 +274,116 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
     store_row(keep, words, row, keepbits, counts, &s_cnt);
 }
 
+// Static top-k / seeded sample for rows of at most 2304 key blocks: ONE wave per row, four rows per workgroup, no LDS and
+// no barrier.  Lane l holds the keys of key blocks l, l + 64, ... in registers, complemented and split into two words
+// (kSlots of them; a key that does not exist or is out of the running is the word pair 0).  The k-th smallest key is
+// found bit by bit from the top: per register one AND, one compare into a lane mask and a population count; the
+// key-index bits above log2(Sb) are zero in every key and skipped, and once a single candidate is left it is the
+// answer.  A ballot of "selected" over the wave IS the pair of keep words of those 64 key blocks.  Same keys, same
+// counts, same comparisons as k_select: the keep bitmaps are identical.  With one workgroup per row, k_select holds
+// 8 rows per CU in flight, each waiting on its barriers; this holds up to 32.
+// grid: ceil(B * masks * Sb / 4).
+constexpr int kWaveSelectMaxSlots = 36;
+static_assert(kWaveSelectMaxSlots <= 64, "one bit per slot in a 64-bit word");
+
+template <int kSlots>
+struct WaveKeys {
+    uint32_t nhi[kSlots], nlo[kSlots];            // ~key, high and low word; (0, 0) = no key here
+};
+
+template <int kSlots>
+__device__ __forceinline__ uint64_t kth_smallest_wave(WaveKeys<kSlots> w, int n, int k, int index_bits) {
+    uint64_t prefix = 0ull;
+    int rank = k, n_alive = n;
+    // one bit of the answer: the candidates with a 0 there are the smaller ones
+    auto step = [&](const uint32_t (&word)[kSlots], uint32_t mask) -> bool {
+        int cnt0 = 0;
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) cnt0 += __popcll(__ballot((word[i] & mask) != 0u));
+        const bool low = rank <= cnt0;            // wave-uniform
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) {
+            const bool zero_here = (word[i] & mask) != 0u;
+            const bool out = low ? !zero_here : zero_here;
+            w.nhi[i] = out ? 0u : w.nhi[i];
+            w.nlo[i] = out ? 0u : w.nlo[i];
+        }
+        if (!low) rank -= cnt0;
+        n_alive = low ? cnt0 : n_alive - cnt0;
+        return !low;
+    };
+    for (int bit = 31; bit >= 0 && n_alive > 1; --bit)
+        if (step(w.nhi, 1u << bit)) prefix |= 1ull << (32 + bit);
+    if (n_alive > 1 && step(w.nlo, 1u << 31)) prefix |= 1ull << 31;
+    for (int bit = index_bits - 1; bit >= 0 && n_alive > 1; --bit)
+        if (step(w.nlo, 1u << bit)) prefix |= 1ull << bit;
+    if (n_alive == 1) {
+        // every live key has a 0 at bit 30, so its complemented low word is not 0: exactly one lane finds its own
+        uint32_t hi = 0u, lo = 0u;
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) { hi |= w.nhi[i]; lo |= w.nlo[i]; }
+        const int src = __ffsll((unsigned long long)__ballot(lo != 0u)) - 1;
+        hi = __shfl(hi, src);
+        lo = __shfl(lo, src);
+        return ~(((uint64_t)hi << 32) | (uint64_t)lo);
+    }
+    return prefix;
+}
+
+template <int kSlots>
+__global__ __launch_bounds__(kThreads) void k_select_wave(const uint8_t* __restrict__ class_map,
+                                                          const float* __restrict__ scores, int64_t rows_total, int Sb,
+                                                          SelectArgs a, uint32_t* __restrict__ keepbits,
+                                                          int32_t* __restrict__ counts) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
+    if (row >= rows_total) return;
+    const int qb = (int)(row % Sb);
+    const float* srow = scores + row * Sb;
+    const uint8_t* crow = class_map + (int64_t)qb * Sb;
+    const int words = (Sb + 31) / 32;
+    int index_bits = 0;
+    while ((1 << index_bits) < Sb) ++index_bits;
+
+    WaveKeys<kSlots> w;
+    uint64_t forced = 0ull;                       // bit i: key block i * 64 + lane is kept whatever its score
+    int n = 0, n_near_cnt = 0;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) {
+        const int kb = i * 64 + lane;
+        const int c = (kb < Sb) ? crow[kb] : 0;
+        const bool selectable = c == 1 || c == 2;
+        const bool far_bit = a.two_ratio && c == 2;
+        uint64_t key = ~0ull;
+        if (selectable) key = (a.mode == 3) ? make_sample_key(a.seed, qb, kb, far_bit) : make_key(srow[kb], kb, far_bit);
+        w.nhi[i] = ~(uint32_t)(key >> 32);
+        w.nlo[i] = ~(uint32_t)key;
+        forced |= (uint64_t)(c == 3 ? 1 : 0) << i;
+        n += __popcll(__ballot(selectable));
+        n_near_cnt += __popcll(__ballot(selectable && c == 1));
+    }
+    uint64_t t_near = 0ull, t_far = 0ull;
+    int k_near = 0, k_far = 0;
+    if (n > 0) {
+        const int n_near = a.two_ratio ? n_near_cnt : n;
+        k_near = keep_count(n_near, a.ratio);
+        k_far = a.two_ratio ? keep_count(n - n_near, a.ratio_far) : 0;
+        if (k_near > 0) t_near = kth_smallest_wave<kSlots>(w, n, k_near, index_bits);
+        if (k_far > 0) t_far = kth_smallest_wave<kSlots>(w, n, n_near + k_far, index_bits);
+    }
+    int kept = 0;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) {
+        const uint64_t key = ~(((uint64_t)w.nhi[i] << 32) | (uint64_t)w.nlo[i]);
+        const bool is_key = w.nlo[i] != 0u, far_key = (key >> 63) != 0;
+        const bool sel = is_key && (far_key ? (k_far > 0 && key <= t_far) : (k_near > 0 && key <= t_near));
+        const uint64_t m = __ballot(sel || ((forced >> i) & 1ull));
+        kept += __popcll(m);
+        if (lane < 2 && 2 * i + lane < words) keepbits[row * words + 2 * i + lane] = (uint32_t)(m >> (32 * lane));
+    }
+    if (lane == 0) counts[row] = kept;
+}
+
 // grid: (Sb, masks, B).  A candidate set of the row is identified by the frame f that realises its gap: the key
 // blocks whose first frame is f (f after the query block) or whose last frame is f (f before it); they lie in the
 // key-block range of frame f, at most `maxlen` blocks.
@@ -472,6 +582,22 @@ hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* cla
 
 hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
                          const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s) {
+    if ((a.mode == 0 || a.mode == 3) && Sb <= 64 * kWaveSelectMaxSlots) {
+        const int64_t rows_total = (int64_t)B * masks * Sb;
+        const dim3 grid((unsigned)((rows_total + kWaves - 1) / kWaves));
+        const int slots = (Sb + 63) / 64;
+#define DR_SELECT_WAVE(S) \
+    hipLaunchKernelGGL(k_select_wave<S>, grid, dim3(kThreads), 0, s, class_map, scores, rows_total, Sb, a, keepbits, counts)
+        if (slots <= 2) DR_SELECT_WAVE(2);
+        else if (slots <= 4) DR_SELECT_WAVE(4);
+        else if (slots <= 8) DR_SELECT_WAVE(8);
+        else if (slots <= 12) DR_SELECT_WAVE(12);
+        else if (slots <= 16) DR_SELECT_WAVE(16);
+        else if (slots <= 24) DR_SELECT_WAVE(24);
+        else DR_SELECT_WAVE(36);
+#undef DR_SELECT_WAVE
+        return hipGetLastError();
+    }
     const size_t words = (Sb + 31) / 32;
     const size_t lds = (size_t)a.sort_cap * (a.mode == 1 ? 16 : 8) + words * 4;
     if (lds > 64 * 1024) {
