@@ -274,7 +274,7 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
     store_row(keep, words, row, keepbits, counts, &s_cnt);
 }
 
-// Static top-k / seeded sample for rows of at most 2304 key blocks: ONE wave per row, four rows per workgroup, no LDS and
+// Static top-k / seeded sample for rows of at most 1024 key blocks: ONE wave per row, four rows per workgroup, no LDS and
 // no barrier.  Lane l holds the keys of key blocks l, l + 64, ... in registers, complemented and split into two words
 // (kSlots of them; a key that does not exist or is out of the running is the word pair 0).  The k-th smallest key is
 // found bit by bit from the top: per register one AND, one compare into a lane mask and a population count; the
@@ -283,7 +283,8 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
 // counts, same comparisons as k_select: the keep bitmaps are identical.  With one workgroup per row, k_select holds
 // 8 rows per CU in flight, each waiting on its barriers; this holds up to 32.
 // grid: ceil(B * masks * Sb / 4).
-constexpr int kWaveSelectMaxSlots = 36;
+constexpr int kWaveSelectMaxSlots = 16;
+constexpr int64_t kWaveSelectMinRows = 2048;
 static_assert(kWaveSelectMaxSlots <= 64, "one bit per slot in a 64-bit word");
 
 template <int kSlots>
@@ -301,12 +302,14 @@ __device__ __forceinline__ uint64_t kth_smallest_wave(WaveKeys<kSlots> w, int n,
 #pragma unroll
         for (int i = 0; i < kSlots; ++i) cnt0 += __popcll(__ballot((word[i] & mask) != 0u));
         const bool low = rank <= cnt0;            // wave-uniform
+        if (cnt0 != 0 && cnt0 != n_alive) {       // otherwise every candidate has the same bit here and all stay
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) {
-            const bool zero_here = (word[i] & mask) != 0u;
-            const bool out = low ? !zero_here : zero_here;
-            w.nhi[i] = out ? 0u : w.nhi[i];
-            w.nlo[i] = out ? 0u : w.nlo[i];
+            for (int i = 0; i < kSlots; ++i) {
+                const bool zero_here = (word[i] & mask) != 0u;
+                const bool out = low ? !zero_here : zero_here;
+                w.nhi[i] = out ? 0u : w.nhi[i];
+                w.nlo[i] = out ? 0u : w.nlo[i];
+            }
         }
         if (!low) rank -= cnt0;
         n_alive = low ? cnt0 : n_alive - cnt0;
@@ -582,8 +585,11 @@ hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* cla
 
 hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
                          const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s) {
-    if ((a.mode == 0 || a.mode == 3) && Sb <= 64 * kWaveSelectMaxSlots) {
-        const int64_t rows_total = (int64_t)B * masks * Sb;
+    // One wave per row pays when there are more rows than workgroups the chip holds at once (per-head masks), and while
+    // a row's keys fit 16 register pairs per lane: measured 15 - 35 % faster than a workgroup per row there, slower
+    // beyond 1024 key blocks (registers, one wave per SIMD) and on the few hundred rows of a single fused mask.
+    const int64_t rows_total = (int64_t)B * masks * Sb;
+    if ((a.mode == 0 || a.mode == 3) && Sb <= 64 * kWaveSelectMaxSlots && rows_total >= kWaveSelectMinRows) {
         const dim3 grid((unsigned)((rows_total + kWaves - 1) / kWaves));
         const int slots = (Sb + 63) / 64;
 #define DR_SELECT_WAVE(S) \
@@ -592,9 +598,7 @@ hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, i
         else if (slots <= 4) DR_SELECT_WAVE(4);
         else if (slots <= 8) DR_SELECT_WAVE(8);
         else if (slots <= 12) DR_SELECT_WAVE(12);
-        else if (slots <= 16) DR_SELECT_WAVE(16);
-        else if (slots <= 24) DR_SELECT_WAVE(24);
-        else DR_SELECT_WAVE(36);
+        else DR_SELECT_WAVE(16);
 #undef DR_SELECT_WAVE
         return hipGetLastError();
     }
@@ -625,11 +629,47 @@ hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, i
     return hipGetLastError();
 }
 
+// The same for rows of at most 2048 key blocks (64 bitmap words): one wave per row, a word per lane, no LDS and no
+// barrier; four rows per workgroup.  grid: ceil(B * masks * Sb / 4).
+__global__ __launch_bounds__(kThreads) void k_emit_wave(const uint32_t* __restrict__ keepbits, int64_t rows_total, int Sb,
+                                                        int shared, const int32_t* __restrict__ rowptr,
+                                                        int32_t* __restrict__ colidx, int64_t capacity) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * kWaves + wave;      // (mask_id, qb) flattened
+    if (r >= rows_total) return;
+    const int64_t mask_id = r / Sb;
+    const int qb = (int)(r - mask_id * Sb);
+    const int64_t row = shared ? qb : r;
+    const int words = (Sb + 31) / 32;
+    const uint32_t wv = (lane < words) ? keepbits[row * words + lane] : 0u;
+    const int c = __popc(wv);
+    int incl = c;
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    long long pos = (long long)rowptr[mask_id * (Sb + 1) + qb] + incl - c;   // negative only past 32-bit offsets
+    int32_t* out = colidx + mask_id * capacity;
+    uint32_t bits = wv;
+    while (bits) {
+        const int bit = __ffs(bits) - 1;
+        bits &= bits - 1;
+        if (pos >= 0 && pos < capacity) out[pos] = lane * 32 + bit;
+        ++pos;
+    }
+}
+
 hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, int masks, int Sb, bool shared,
                        int32_t* rowptr, int32_t* colidx, int64_t capacity, int64_t* nnz, hipStream_t s) {
     hipLaunchKernelGGL(k_row_offsets, dim3(masks, B), dim3(kThreads), 0, s, counts, masks, Sb, shared ? 1 : 0, rowptr, nnz);
-    hipLaunchKernelGGL(k_emit, dim3(Sb, masks, B), dim3(kThreads), 0, s, keepbits, masks, Sb, shared ? 1 : 0, rowptr, colidx,
-                       capacity);
+    if (Sb <= 64 * 32) {
+        const int64_t rows_total = (int64_t)B * masks * Sb;
+        hipLaunchKernelGGL(k_emit_wave, dim3((unsigned)((rows_total + kWaves - 1) / kWaves)), dim3(kThreads), 0, s, keepbits,
+                           rows_total, Sb, shared ? 1 : 0, rowptr, colidx, capacity);
+    } else {
+        hipLaunchKernelGGL(k_emit, dim3(Sb, masks, B), dim3(kThreads), 0, s, keepbits, masks, Sb, shared ? 1 : 0, rowptr,
+                           colidx, capacity);
+    }
     return hipGetLastError();
 }
 

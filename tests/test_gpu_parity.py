@@ -112,36 +112,40 @@ def test_masks_two_ratio_and_ties():
                            oracle_masks_from(q, cls, mode, par, 0.25 if mode == "static" else None))
 
 
-# row lengths on both sides of every width the per-wave selection is built for (64 key blocks per register slot:
-# 2, 4, 8, 12, 16, 24 and 36 slots), and beyond the last, where one workgroup per row selects through LDS
+# Static top-k and the uniform sample run one wave per row when a row has at most 1024 key blocks (64 per register slot:
+# 2, 4, 8, 12 or 16 slots) and the call has at least 2048 rows, else one workgroup per row through LDS: row lengths on
+# both sides of every slot width, each with one mask (LDS) and with enough per-head masks to cross the row threshold
+# (the bitmap becomes the column list one wave per row up to 2048 key blocks, one workgroup per row beyond)
 @pytest.mark.parametrize("grid", [(6, 8, 8), (8, 16, 16), (9, 16, 16), (8, 32, 32), (12, 32, 32), (13, 32, 32), (24, 32, 32),
-                                  (32, 32, 32), (11, 40, 80), (21, 40, 80), (24, 48, 64), (5, 2, 7373), (27, 48, 64)],
+                                  (25, 32, 32), (32, 32, 32), (11, 40, 80), (64, 32, 32), (21, 40, 80)],
                          ids=lambda g: f"Sb{-(-g[0] * g[1] * g[2] // 32)}")
 def test_static_and_uniform_selection_across_row_lengths(grid):
     Nf, Hg, Wg = grid
-    wl = Workload("rows", 21, 1, 1, 64, Nf, Hg, Wg, 32, "f32", "iid", "static", 0.3, None, 1.0)
-    Sb = wl.Sb
-    L0 = 1 << (wl.Nt - 1).bit_length()
-    g = torch.Generator().manual_seed(Sb)
-    scores = torch.randn((1, 1, Sb, Sb), generator=g, dtype=torch.float32)
-    scores[0, 0, 1::2] = (scores[0, 0, 1::2] * 2.0).round() * 0.5          # every other row: many equal scores,
-    scores[0, 0, 1::4] = scores[0, 0, 1::4].abs() * -1.0                   # and in every fourth only zeros of sign minus
-    scores = scores.cuda()
+    Sb = -(-Nf * Hg * Wg // 32)
+    L0 = 1 << (Hg * Wg - 1).bit_length()
     shape_only = np.zeros((1, 1, Sb, Sb), dtype=np.float32)
-    # a wide window: many selectable blocks per row, one class; a decay length that crosses the block size between
-    # frame distances 3 and 4 (Eq. 2): both classes, ranked separately
-    for gamma, far_ratios in ((3.0, (-1.0,)), (192.0 / L0, (0.05, 1.0))):
-        cls = oracle_class_map(wl, gamma=gamma)
-        assert (cls == 1).any() and (gamma == 3.0 or (cls == 2).any())
-        for ratio_far in far_ratios:
-            for ratio, seed in ((0.3, 7), (1e-4, 20470)):
-                run = GpuRun(wl, params=dr.MaskParams(gamma=gamma, ratio_far=ratio_far, seed=seed, head_fuse=1))
-                rowptr, colidx, nnz, cap = run.build_mask(scores, "static", ratio)
-                assert_masks_equal(rowptr, colidx, nnz,
-                                   oracle_masks_from(scores, cls, "static", ratio, ratio_far if ratio_far >= 0 else None))
-                rowptr, colidx, nnz, cap = run.build_mask(None, "uniform", ratio)
-                assert_masks_equal(rowptr, colidx, nnz,
-                                   o.build_mask(shape_only, cls, "uniform", ratio, ratio_far=ratio_far, seed=seed))
+    for H in sorted({1, -(-2048 // Sb)}):
+        wl = Workload("rows", 21, 1, H, 64, Nf, Hg, Wg, 32, "f32", "iid", "static", 0.3, None, 1.0)
+        g = torch.Generator().manual_seed(Sb + H)
+        scores = torch.randn((1, H, Sb, Sb), generator=g, dtype=torch.float32)
+        scores[0, :, 1::2] = (scores[0, :, 1::2] * 2.0).round() * 0.5      # every other row: many equal scores,
+        scores[0, :, 1::4] = scores[0, :, 1::4].abs() * -1.0               # and in every fourth only zeros of sign minus
+        scores = scores.cuda()
+        # a wide window: many selectable blocks per row, one class; a decay length that crosses the block size between
+        # frame distances 3 and 4 (Eq. 2): both classes, ranked separately
+        for gamma, far_ratios in ((3.0, (-1.0,)), (192.0 / L0, (0.05, 1.0))):
+            cls = oracle_class_map(wl, gamma=gamma)
+            assert (cls == 1).any() and (gamma == 3.0 or (cls == 2).any())
+            for ratio_far in far_ratios:
+                for ratio, seed in ((0.3, 7), (1e-4, 20470)):
+                    run = GpuRun(wl, params=dr.MaskParams(gamma=gamma, ratio_far=ratio_far, seed=seed,
+                                                          head_fuse=1 if H == 1 else 0))
+                    rowptr, colidx, nnz, cap = run.build_mask(scores, "static", ratio)
+                    assert_masks_equal(rowptr, colidx, nnz, oracle_masks_from(scores, cls, "static", ratio,
+                                                                              ratio_far if ratio_far >= 0 else None))
+                    rowptr, colidx, nnz, cap = run.build_mask(None, "uniform", ratio)
+                    want = o.build_mask(shape_only, cls, "uniform", ratio, ratio_far=ratio_far, seed=seed)
+                    assert_masks_equal(rowptr, colidx, nnz, [[want[0][0]] * run.masks])
 
 
 def test_mask_capacity_overflow_is_reported_not_written():
