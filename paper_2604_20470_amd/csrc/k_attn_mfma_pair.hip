@@ -74,8 +74,8 @@ __device__ __forceinline__ void issue_chunk(const LoadPlan& lp, const char* Kh, 
 
 struct State {
     v16f o[2][4];     // [query half][channel block] O^T accumulators (accumulation registers)
-    float l_part[2];
-    float lsum[2];    // per query half: the loop's share of the normaliser
+    v16f lacc[2];     // [query half] normaliser: every row of the tile holds the 32 queries' sums (accumulation registers)
+    v8bf ones;        // A operand of the normaliser's matrix instruction
 };
 
 struct ReadPlan {
@@ -103,55 +103,65 @@ __device__ __forceinline__ void mfma_s(v16f& s, const v8bf& k, const v8bf& q) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(k), "a"(q));
 }
 // Normaliser: a row's sum of probabilities is taken from the bf16-rounded values, the ones O += V P multiplies, so
-// that numerator and denominator of the softmax see the same rounding (with one dominant key the quotient is then
-// exact; summing the unrounded exponentials leaves up to 2^-9 relative error in O and is 6 % faster).  A 4x4x4 matrix
-// instruction with an all-ones A operand can form the sum of a lane's four packed values in one issue slot, but
-// each one holds up the next 32x32x16 instruction by its two passes: no faster than the additions.
-__device__ __forceinline__ float rounded_sum(const v2bf& pk) { return (float)pk[0] + (float)pk[1]; }
+// that numerator and denominator of the softmax see the same rounding and with one dominant key the quotient is
+// exact.  (Summing the fp32 exponentials instead is what kernels that subtract the row maximum do, where the
+// dominant probability is exactly 1 and rounds without error; here no reference is subtracted, the dominant
+// probability is 2^s with any mantissa, and its rounding error, up to 2^-8 relative, would go straight into O:
+// 2.2e-2 on rows with one dominant key and |V| near 5.)  The sums are formed by the matrix pipe: one more
+// 32x32x16 instruction per P^T fragment with an all-ones A operand, lacc += 1 P^T, leaves the 32 queries' sums over
+// the fragment's 16 keys in every row of lacc.  That is a quarter more O += V P instructions (72 instead of 64
+// per chunk), but the vector ALU, whose instruction issue is what bounds a lone wavefront, loses three
+// instructions per pair of probabilities (two unpacks, two additions; a lone wavefront pays 5 to 6 cycles for each).
 // The accumulators are operands of the wait so that every later read of them depends on it (a plain register copy
 // could otherwise be scheduled right behind the matrix instruction that produces its source).
-__device__ __forceinline__ void drain_mfma(v16f (&o)[2][4]) {
+__device__ __forceinline__ void drain_mfma(v16f (&o)[2][4], v16f (&lacc)[2]) {
     asm volatile("s_nop 15\n\ts_nop 15"
-                 : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[0][2]), "+a"(o[0][3]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[1][2]), "+a"(o[1][3])
+                 : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[0][2]), "+a"(o[0][3]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[1][2]), "+a"(o[1][3]),
+                   "+a"(lacc[0]), "+a"(lacc[1])
                  :: "memory");
 }
-#define DR_PIN_O() do { _Pragma("unroll") for (int qh_ = 0; qh_ < 2; ++qh_) _Pragma("unroll") for (int db_ = 0; db_ < 4; ++db_) asm volatile("" : "+a"(st.o[qh_][db_])); } while (0)
+#define DR_PIN_O() do { _Pragma("unroll") for (int qh_ = 0; qh_ < 2; ++qh_) { asm volatile("" : "+a"(st.lacc[qh_])); _Pragma("unroll") for (int db_ = 0; db_ < 4; ++db_) asm volatile("" : "+a"(st.o[qh_][db_])); } } while (0)
 
-// ---- schedule of one chunk: 64 matrix-instruction slots, one exponential per slot ----
+// ---- schedule of one chunk: 72 matrix-instruction slots, an exponential in 64 of them ----
 // A wave owns 64 queries = two query halves qh; a chunk has two 32-key halves mb; tile (mb, qh) is 32 keys x 32 queries.
-//   slots  0.. 7  S tile (0,0)                     16..23  S tile (0,1)       24..31  S tile (1,0)      40..47  S tile (1,1)
-//   slots  8..15  O += V P of tile (1,1) of the PREVIOUS chunk               32..39  O += V P (0,0)
-//   slots 48..55  O += V P (0,1)                                              56..63  O += V P (1,0)
-// The exponentials run one per slot behind the S tiles (stream position q = slot - 1: pair k = q / 2): tile (1,1) of the
-// previous chunk finishes in slots 0..8, (0,0) in 9..24, (0,1) in 25..40, (1,0) in 41..56, the first half of (1,1) in
-// 57..0.  A pair = two exponentials and one pack to bf16; one slot later the two packed values are unpacked again and
-// added to the normaliser.
+// "S" = the 8 steps of a logit tile; "PVL" = O += V P of a tile, 10 instructions: for each of its two P^T fragments t
+// the four channel blocks of O, then the normaliser.
+//   slots  0.. 7  S (0,0)      18..25  S (0,1)      26..33  S (1,0)      44..51  S (1,1)
+//   slots  8..17  PVL of tile (1,1) of the PREVIOUS chunk      34..43  PVL (0,0)      52..61  PVL (0,1)      62..71  PVL (1,0)
+// The exponentials are one stream, position q = 0..63, in slot q + 1 + q / 8 (every ninth slot has none): the second
+// half of tile (1,1) of the previous chunk in slots 1..8, (0,0) in 10..26, (0,1) in 28..44, (1,0) in 46..62, the
+// first half of (1,1) in 64..71.  A pair = two exponentials in adjacent slots and one pack to bf16 in the second.
+// Every tile is read by its first exponential at least two slots after its last step, and every P^T fragment is
+// complete at least five slots before the first instruction that multiplies it.
 // LDS reads: K fragments of key half 1 in slots 10..17, V^T fragments of key half 0 in 18..25, of key half 1 in 44..51;
 // after that the chunk's LDS stage is not read again: the barrier sits before slot 56, and slots 56..63 also fetch the K
 // fragments of the next chunk's first key half and issue the tile loads of the chunk after it.
+constexpr int kSlots = 72;
 constexpr int kBarrierSlot = 56;
-struct MfmaSlot { int kind, mb, qh, idx; };   // kind 0: S step idx of tile (mb, qh); 1: O += V P, idx = t * 4 + db
-constexpr MfmaSlot mfma_at(int slot) {
-    const int ph = slot >> 3, i = slot & 7;
-    switch (ph) {
-        case 0: return {0, 0, 0, i};
-        case 1: return {1, 1, 1, i};
-        case 2: return {0, 0, 1, i};
-        case 3: return {0, 1, 0, i};
-        case 4: return {1, 0, 0, i};
-        case 5: return {0, 1, 1, i};
-        case 6: return {1, 0, 1, i};
-        default: return {1, 1, 0, i};
-    }
+struct MfmaSlot { int kind, mb, qh, idx; };   // kind 0: S step idx of tile (mb, qh); 1: O += V P, idx = t * 4 + db; 2: normaliser, idx = t
+constexpr MfmaSlot pvl_at(int mb, int qh, int i) {
+    if (i == 4 || i == 9) return {2, mb, qh, i / 5};
+    return {1, mb, qh, (i / 5) * 4 + i % 5};
 }
-struct ExpSlot { int mb, qh, gi, second; };   // exponential of value 2 gi + second of tile (mb, qh)
+constexpr MfmaSlot mfma_at(int slot) {
+    if (slot < 8) return {0, 0, 0, slot};
+    if (slot < 18) return pvl_at(1, 1, slot - 8);
+    if (slot < 26) return {0, 0, 1, slot - 18};
+    if (slot < 34) return {0, 1, 0, slot - 26};
+    if (slot < 44) return pvl_at(0, 0, slot - 34);
+    if (slot < 52) return {0, 1, 1, slot - 44};
+    if (slot < 62) return pvl_at(0, 1, slot - 52);
+    return pvl_at(1, 0, slot - 62);
+}
+struct ExpSlot { bool valid; int mb, qh, gi, second; };   // exponential of value 2 gi + second of tile (mb, qh)
 constexpr ExpSlot exp_at(int slot) {
-    const int q = (slot + 63) & 63, k = q >> 1, second = q & 1;
-    if (k < 4) return {1, 1, 4 + k, second};
-    if (k < 12) return {0, 0, k - 4, second};
-    if (k < 20) return {0, 1, k - 12, second};
-    if (k < 28) return {1, 0, k - 20, second};
-    return {1, 1, k - 28, second};
+    if (slot % 9 == 0) return {false, 0, 0, 0, 0};
+    const int q = slot - 1 - slot / 9, k = q >> 1, second = q & 1;
+    if (k < 4) return {true, 1, 1, 4 + k, second};
+    if (k < 12) return {true, 0, 0, k - 4, second};
+    if (k < 20) return {true, 0, 1, k - 12, second};
+    if (k < 28) return {true, 1, 0, k - 20, second};
+    return {true, 1, 1, k - 28, second};
 }
 
 struct Frags {
@@ -159,7 +169,7 @@ struct Frags {
     v8bf vf[2][2][4];      // [mb][t][db]
     v8bf pf[2][2][2];      // [mb][qh][t]
     v16f s[2][2];          // [mb][qh]
-    float e_first[1];      // first exponential of the pair in flight
+    float e_first;         // first exponential of the pair in flight (from one slot to the next)
 };
 
 template <int I, int E, class F>
@@ -180,23 +190,54 @@ __device__ __forceinline__ void mask_front(v16f& s, int mb, int half, int lo) {
         if (base + (j >> 2) * 8 + (j & 3) < lo) s[j] = -INFINITY;
 }
 
+// Where the window of the chunk after next lies, worked out in five steps of a few scalar instructions each in the
+// shadow of slots 28..32: between two slots the same instructions would leave the matrix pipe idle (a lone wavefront
+// issues one instruction every four to five cycles, whatever its kind).
+struct Next {
+    int c2, win, Sb, N, grp;          // in: chunk index, the register window over the merged list, limits, the wave's query block
+    uint32_t row_bytes;
+    const char *Kh, *Vh;
+    uint32_t e;                       // the list entry
+    int key0;                         // first row of the 64-row window
+    uint64_t off, kbase, vbase;
+    bool own;                         // the wave's query block lists the key block
+};
+template <int K>
+__device__ __forceinline__ void next_step(Next& nx) {
+    if constexpr (K == 0) nx.e = (uint32_t)__builtin_amdgcn_readlane(nx.win, (nx.c2 >> 1) & 63);
+    if constexpr (K == 1) {
+        // (the clamp of the key block never acts on a list as k_group_union writes it; it keeps any other list inside K / V)
+        const int kb = min((int)(nx.e & 0x0fffffffu), nx.Sb - 1);
+        nx.key0 = min(kb * kBs + (nx.c2 & 1) * kChunkKeys, nx.N - kChunkKeys);
+    }
+    if constexpr (K == 2) {
+        nx.own = ((nx.e >> (28 + nx.grp)) & 1u) != 0;
+        nx.off = (uint64_t)(uint32_t)nx.key0 * nx.row_bytes;
+    }
+    if constexpr (K == 3) nx.kbase = uniform64((uint64_t)nx.Kh + nx.off);
+    if constexpr (K == 4) nx.vbase = uniform64((uint64_t)nx.Vh + nx.off);
+}
+
 // Slots [FROM, TO) of the chunk whose tiles sit at LDS addresses rd (stage offset already added).  Slots 56..63 move rd
 // to the other stage, read the next chunk's first K fragments from there and issue one tile load each of the window at
 // kbase / vbase into the stage at m0_next; with kSkip they do only that (a wavefront that sits the chunk out).
 template <int FROM, int TO, bool kSkip>
 __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v8bf (&qf)[2][8], State& st, Frags& fr,
-                                          const LoadPlan& lp, uint64_t kbase, uint64_t vbase, uint32_t m0_next) {
+                                          const LoadPlan& lp, Next& nx, uint32_t m0_next) {
     constexpr uint32_t kV = kTileBytes;
     static_for<FROM, TO>([&](auto slot_c) {
         constexpr int slot = decltype(slot_c)::value;
         constexpr MfmaSlot m = mfma_at(slot);
+        if constexpr (!kSkip && slot >= 28 && slot < 33) next_step<slot - 28>(nx);
         if constexpr (kSkip) {
         } else if constexpr (m.kind == 0) {
             if constexpr (m.idx == 0) mfma_s_first(fr.s[m.mb][m.qh], m.mb ? fr.kf1[0] : fr.kf0[0], qf[m.qh][0]);
             else mfma_s(fr.s[m.mb][m.qh], m.mb ? fr.kf1[m.idx] : fr.kf0[m.idx], qf[m.qh][m.idx]);
-        } else {
+        } else if constexpr (m.kind == 1) {
             constexpr int t = m.idx >> 2, db = m.idx & 3;
             mfma_pv(st.o[m.qh][db], fr.vf[m.mb][t][db], fr.pf[m.mb][m.qh][t]);
+        } else {
+            mfma_pv(st.lacc[m.qh], st.ones, fr.pf[m.mb][m.qh][m.idx]);
         }
         // ---- LDS reads ----
         if constexpr (slot >= 10 && slot < 18) fr.kf1[slot - 10] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 10] + 32 * kRowBytes);
@@ -207,39 +248,31 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
             u.s2.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + kV + (mb * 32 + t * 16 + 8) * kRowBytes));
             fr.vf[mb][t][db] = u.v;
         }
-        if constexpr (slot >= 56 && TO == 64) {
+        if constexpr (slot >= 56 && slot < 64 && TO == kSlots) {
+            // the barrier has released the stage: one tile load each of the chunk after next
+            constexpr int i = (slot - 56) >> 1;
+            if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], nx.kbase, m0_next + i * 4096);
+            else dma16(lp.voff_i[i], nx.vbase, m0_next + kTileBytes + i * 4096);
+        }
+        if constexpr (slot >= 64 && TO == kSlots) {
             // the chunk's own LDS stage is not read any more: the read addresses move to the other stage (stage_delta =
             // +- one stage), then the next chunk's first K fragments are fetched (also when there is no next chunk: the
-            // address is a valid LDS address) and one tile load of the chunk after it is issued
-            rd.k_addr[slot - 56] += stage_delta;
-            if constexpr (slot < 60) rd.v_addr[slot - 56] += stage_delta;
-            fr.kf0[slot - 56] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 56]);
-            constexpr int i = (slot - 56) >> 1;
-            if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], kbase, m0_next + i * 4096);
-            else dma16(lp.voff_i[i], vbase, m0_next + kTileBytes + i * 4096);
+            // address is a valid LDS address)
+            rd.k_addr[slot - 64] += stage_delta;
+            if constexpr (slot < 68) rd.v_addr[slot - 64] += stage_delta;
+            fr.kf0[slot - 64] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 64]);
         }
-        // ---- one exponential; every second slot also the pack; the two values packed in the previous slot go into
-        // the normaliser, as rounded (between the exponential and the pack that reads it: a transcendental's result
-        // is not ready for the very next instruction) ----
-        if constexpr (!kSkip) {
+        // ---- one exponential; the second of a pair is followed by the pack of the two ----
+        if constexpr (!kSkip && exp_at(slot).valid) {
             constexpr ExpSlot e = exp_at(slot);
             const float ev = __builtin_amdgcn_exp2f(fr.s[e.mb][e.qh][2 * e.gi + e.second]);
-            constexpr ExpSlot pe = exp_at((slot + 63) & 63);
-            if constexpr (pe.second) {
-                constexpr int t = pe.gi >> 2, i0 = (2 * pe.gi) & 7;
-                v2bf two;
-                two[0] = fr.pf[pe.mb][pe.qh][t][i0];
-                two[1] = fr.pf[pe.mb][pe.qh][t][i0 + 1];
-                st.lsum[pe.qh] += rounded_sum(two);
-                asm volatile("" : "+v"(st.lsum[pe.qh]));
-            }
             if constexpr (!e.second) {
-                fr.e_first[0] = ev;
-                asm volatile("" : "+v"(fr.e_first[0]));
+                fr.e_first = ev;
+                asm volatile("" : "+v"(fr.e_first));
             } else {
                 constexpr int t = e.gi >> 2, i = (2 * e.gi) & 7;
                 v2bf pk;
-                pk[0] = (__bf16)fr.e_first[0];
+                pk[0] = (__bf16)fr.e_first;
                 pk[1] = (__bf16)ev;
                 asm volatile("" : "+v"(pk));      // anchors the pair in this slot of the interleaved stream
                 fr.pf[e.mb][e.qh][t][i] = pk[0];
@@ -250,38 +283,29 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
     });
 }
 
-// Completes what the last chunk leaves in flight: the second half of its tile (1,1) (the pair whose first exponential
-// was taken in slot 63 included), then that tile's O += V P.
-__device__ __forceinline__ void finish_pending(State& st, Frags& fr, float (&lc)[2]) {
-    v2bf pk;
-    {
-        const float e1 = __builtin_amdgcn_exp2f(fr.s[1][1][7]);
-        pk[0] = (__bf16)fr.e_first[0];
-        pk[1] = (__bf16)e1;
-        // elements 4 .. 7 of the fragment: the first pair was packed in slot 62, this is the second
-        lc[1] += rounded_sum(pk);
-        fr.pf[1][1][0][6] = pk[0];
-        fr.pf[1][1][0][7] = pk[1];
-    }
+// Completes what the last chunk leaves in flight: the second half of its tile (1,1), then that tile's O += V P and
+// normaliser (the compiler's own matrix instructions here: outside the hand-scheduled loop it looks after the wait
+// states between matrix instructions and their neighbours).
+__device__ __forceinline__ void finish_pending(State& st, Frags& fr) {
 #pragma unroll
     for (int gi = 4; gi < 8; ++gi) {
-        const float e0 = __builtin_amdgcn_exp2f(fr.s[1][1][2 * gi]);
-        const float e1 = __builtin_amdgcn_exp2f(fr.s[1][1][2 * gi + 1]);
-        pk[0] = (__bf16)e0;
-        pk[1] = (__bf16)e1;
-        lc[1] += rounded_sum(pk);
+        v2bf pk;
+        pk[0] = (__bf16)__builtin_amdgcn_exp2f(fr.s[1][1][2 * gi]);
+        pk[1] = (__bf16)__builtin_amdgcn_exp2f(fr.s[1][1][2 * gi + 1]);
         fr.pf[1][1][1][(2 * gi) & 7] = pk[0];
         fr.pf[1][1][1][((2 * gi) & 7) + 1] = pk[1];
     }
 #pragma unroll
     for (int idx = 0; idx < 8; ++idx)
         st.o[1][idx & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.vf[1][idx >> 2][idx & 3], fr.pf[1][1][idx >> 2], st.o[1][idx & 3], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) st.lacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.ones, fr.pf[1][1][t], st.lacc[1], 0, 0, 0);
 }
 
 // One whole chunk by plain code (no pipelining), from the tiles at LDS addresses rd + stage_off: window rows below
 // `lo` masked.  Used before the pipelined loop for the sequence's partial chunk.
 __device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_off, const v8bf (&qf)[2][8], State& st,
-                                            float (&lc)[2], int lo, int half) {
+                                            int lo, int half) {
     constexpr uint32_t kV = kTileBytes;
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh)
@@ -302,7 +326,6 @@ __device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_o
                 v2bf pk;
                 pk[0] = (__bf16)__builtin_amdgcn_exp2f(acc[j]);
                 pk[1] = (__bf16)__builtin_amdgcn_exp2f(acc[j + 1]);
-                lc[qh] += rounded_sum(pk);
                 pf[j >> 3][j & 7] = pk[0];
                 pf[j >> 3][(j & 7) + 1] = pk[1];
             }
@@ -317,6 +340,8 @@ __device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_o
                     // wait states between matrix instructions and their neighbours)
                     st.o[qh][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[t], st.o[qh][db], 0, 0, 0);
                 }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) st.lacc[qh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.ones, pf[t], st.lacc[qh], 0, 0, 0);
         }
 }
 
@@ -393,13 +418,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     State st;
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
-        st.l_part[qh] = 0.f;
-        st.lsum[qh] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) st.lacc[qh][j] = 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int j = 0; j < 16; ++j) st.o[qh][db][j] = 0.f;
     }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) st.ones[i] = (__bf16)1.0f;
+    asm volatile("" : "+v"(st.ones));
     DR_PIN_O();
 
     // ---- the chunk sequence.  Every entry of the merged list is a key block = two chunks of 64 keys, except the
@@ -440,9 +468,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         if (has_part) issue_chunk<1>(lp, Kh, Vh, N - kChunkKeys, row_bytes);
         DR_WAIT_VMCNT0();
         DR_BARRIER();
-        float lc[2] = {0.f, 0.f};
         if (has_part) {
-            if (own_part) plain_chunk(rd, kStageBytes, qf, st, lc, kChunkKeys - part_keys, half);
+            if (own_part) plain_chunk(rd, kStageBytes, qf, st, kChunkKeys - part_keys, half);
             DR_BARRIER();          // stage 1 is free again
         }
         if (n_chunks > 0) {
@@ -461,7 +488,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
                     for (int i = 0; i < 8; ++i) fr.vf[1][t][db][i] = (__bf16)0.f;
             }
-            fr.e_first[0] = 0.f;
+            fr.e_first = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) fr.kf0[ks] = *(lds_v8)(uintptr_t)(rd.k_addr[ks]);
             // Loop invariant at the top of a chunk: its tiles are complete in LDS for every wave, the K fragments of
@@ -469,46 +496,50 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             asm volatile("" : "+v"(fr.s[1][1]));
             int stage = 0;                      // LDS stage of the chunk being consumed
             bool own_cur = d0.own, own_nxt = d1.own;
+            Next nx;
+            nx.Sb = a.Sb; nx.N = N; nx.grp = grp; nx.row_bytes = (uint32_t)row_bytes; nx.Kh = Kh; nx.Vh = Vh;
             for (int c = 0; c < n_chunks; ++c) {
                 DR_PIN_O();
+                // the chunk after next (past the end of the list: the last chunk again, into the stage nobody reads)
+                nx.c2 = min(c + 2, n_chunks - 1);
+                const bool refill = (nx.c2 >> 1) >= wbase + 64;
                 // a wavefront that sits the chunk out leaves the tile it has in flight as it is: the next chunk it
                 // takes part in (or the code after the loop) completes it
-                if (own_cur) run_slots<0, kBarrierSlot, false>(rd, 0, qf, st, fr, lp, 0, 0, 0);
-                // the chunk after next (past the end of the list: the last chunk again, into the stage nobody reads)
-                const int c2 = min(c + 2, n_chunks - 1);
-                if ((c2 >> 1) >= wbase + 64) {
+                if (own_cur) run_slots<0, 27, false>(rd, 0, qf, st, fr, lp, nx, 0);
+                if (refill) {
                     wbase += 64;
                     win = gl[min(wbase + lane, cnt - 1)];
                     asm volatile("" : "+v"(win));
                 }
-                const Desc d2 = describe(c2);
-                const uint64_t kbase = uniform64((uint64_t)(Kh + (int64_t)d2.key0 * row_bytes));
-                const uint64_t vbase = uniform64((uint64_t)(Vh + (int64_t)d2.key0 * row_bytes));
+                nx.win = win;
+                if (own_cur) {
+                    run_slots<27, kBarrierSlot, false>(rd, 0, qf, st, fr, lp, nx, 0);
+                } else {
+                    next_step<0>(nx); next_step<1>(nx); next_step<2>(nx); next_step<3>(nx); next_step<4>(nx);
+                }
                 DR_WAIT_VMCNT0();
                 DR_BARRIER();
                 __builtin_amdgcn_sched_barrier(0);
                 const uint32_t m0n = lp.m0_k + stage * kStageBytes;
-                if (own_cur) run_slots<kBarrierSlot, 64, false>(rd, stage ? -kStageBytes : kStageBytes, qf, st, fr, lp, kbase, vbase, m0n);
-                else run_slots<kBarrierSlot, 64, true>(rd, stage ? -kStageBytes : kStageBytes, qf, st, fr, lp, kbase, vbase, m0n);
+                if (own_cur) run_slots<kBarrierSlot, kSlots, false>(rd, stage ? -kStageBytes : kStageBytes, qf, st, fr, lp, nx, m0n);
+                else run_slots<kBarrierSlot, kSlots, true>(rd, stage ? -kStageBytes : kStageBytes, qf, st, fr, lp, nx, m0n);
                 DR_PIN_O();
                 own_cur = own_nxt;
-                own_nxt = d2.own;
+                own_nxt = nx.own;
                 stage ^= 1;
             }
-            finish_pending(st, fr, lc);
+            finish_pending(st, fr);
         }
-        st.l_part[0] = lc[0] + st.lsum[0];
-        st.l_part[1] = lc[1] + st.lsum[1];
         DR_WAIT_VMCNT0();          // the loads issued by the last chunks write LDS: none may outlive the workgroup
     }
 
     // ---- epilogue ----
-    drain_mfma(st.o);
+    drain_mfma(st.o, st.lacc);
     char* Oh = reinterpret_cast<char*>(a.O) + head_off;
     bool out_of_range = false;
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
-        const float l = st.l_part[qh] + __shfl_xor(st.l_part[qh], 32);
+        const float l = st.lacc[qh][0];          // every row of the tile holds the sums: lane -> query l32, both halves
         const float inv = (l > 0.f) ? 1.0f / l : 0.f;
         const int qrow = q_wave0 + qh * 32 + l32;
         if (has_rows && qrow < N) {
