@@ -130,9 +130,10 @@ __device__ __forceinline__ void drain_mfma(v16f (&o)[2][4], v16f (&lacc)[2]) {
 //   slots  8..17  PVL of tile (1,1) of the PREVIOUS chunk      34..43  PVL (0,0)      52..61  PVL (0,1)      62..71  PVL (1,0)
 // The exponentials are one stream, position q = 0..63, in slot q + 1 + q / 8 (every ninth slot has none): the second
 // half of tile (1,1) of the previous chunk in slots 1..8, (0,0) in 10..26, (0,1) in 28..44, (1,0) in 46..62, the
-// first half of (1,1) in 64..71.  A pair = two exponentials in adjacent slots and one pack to bf16 in the second.
+// first half of (1,1) in 64..71.  A pair = two exponentials in adjacent slots and one pack to bf16 in the slot after
+// (the last pair of a chunk is packed in slot 0 of the next chunk the wavefront takes part in, or after the loop).
 // Every tile is read by its first exponential at least two slots after its last step, and every P^T fragment is
-// complete at least five slots before the first instruction that multiplies it.
+// complete at least four slots before the first instruction that multiplies it.
 // LDS reads: K fragments of key half 1 in slots 10..17, V^T fragments of key half 0 in 18..25, of key half 1 in 44..51;
 // after that the chunk's LDS stage is not read again: the barrier sits before slot 56, and slots 56..63 also fetch the K
 // fragments of the next chunk's first key half and issue the tile loads of the chunk after it.
@@ -169,7 +170,7 @@ struct Frags {
     v8bf vf[2][2][4];      // [mb][t][db]
     v8bf pf[2][2][2];      // [mb][qh][t]
     v16f s[2][2];          // [mb][qh]
-    float e_first;         // first exponential of the pair in flight (from one slot to the next)
+    float e_pair[2];       // the pair of exponentials in flight: packed in the slot after the second was taken
 };
 
 template <int I, int E, class F>
@@ -218,6 +219,19 @@ __device__ __forceinline__ void next_step(Next& nx) {
     if constexpr (K == 4) nx.vbase = uniform64((uint64_t)nx.Vh + nx.off);
 }
 
+// A tile load in two parts, so that the matrix instruction and the exponential of the slot sit between the write of m0
+// and the load that reads it (the one wait state that needs) instead of a no-op, and m0 is written by the addition itself.
+template <uint32_t OFF>
+__device__ __forceinline__ void set_m0(uint32_t base) {
+    asm volatile("s_add_i32 m0, %0, %1" :: "s"(base), "n"(OFF) : "m0", "scc");
+}
+__device__ __forceinline__ void dma16_go(uint32_t voff, uint64_t base) {
+    asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(voff), "s"(base) : "memory");
+}
+// s_waitcnt lgkmcnt(n) alone (vmcnt and expcnt fields at their maxima): placed where a whole batch of LDS reads is known
+// to have had time to arrive, one wait replaces the one per fragment the compiler would otherwise put before every use.
+#define DR_WAIT_LGKM(n) __builtin_amdgcn_s_waitcnt(0xC07F | ((n) << 8))
+
 // Slots [FROM, TO) of the chunk whose tiles sit at LDS addresses rd (stage offset already added).  Slots 56..63 move rd
 // to the other stage, read the next chunk's first K fragments from there and issue one tile load each of the window at
 // kbase / vbase into the stage at m0_next; with kSkip they do only that (a wavefront that sits the chunk out).
@@ -229,6 +243,19 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
         constexpr int slot = decltype(slot_c)::value;
         constexpr MfmaSlot m = mfma_at(slot);
         if constexpr (!kSkip && slot >= 28 && slot < 33) next_step<slot - 28>(nx);
+        if constexpr (!kSkip) {
+            // K fragments of key half 0 (read in slots 60..67 of the previous chunk); of key half 1 (slots 10..17: at most
+            // the 16 V^T reads behind them are still out); V^T of key half 0 (18..25); of key half 1 (44..51: only
+            // the two K reads of slots 60, 61 are younger)
+            if constexpr (slot == 0) DR_WAIT_LGKM(0);
+            if constexpr (slot == 26) DR_WAIT_LGKM(15);
+            if constexpr (slot == 34) DR_WAIT_LGKM(0);
+            if constexpr (slot == 62) DR_WAIT_LGKM(2);
+        }
+        if constexpr (!kSkip && slot >= 56 && slot < 64 && TO == kSlots) {
+            constexpr int i = (slot - 56) >> 1;
+            set_m0<((slot & 1) ? kTileBytes : 0) + i * 4096>(m0_next);
+        }
         if constexpr (kSkip) {
         } else if constexpr (m.kind == 0) {
             if constexpr (m.idx == 0) mfma_s_first(fr.s[m.mb][m.qh], m.mb ? fr.kf1[0] : fr.kf0[0], qf[m.qh][0]);
@@ -248,35 +275,44 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
             u.s2.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(uintptr_t)(rd.v_addr[db] + kV + (mb * 32 + t * 16 + 8) * kRowBytes));
             fr.vf[mb][t][db] = u.v;
         }
-        if constexpr (slot >= 56 && slot < 64 && TO == kSlots) {
-            // the barrier has released the stage: one tile load each of the chunk after next
-            constexpr int i = (slot - 56) >> 1;
-            if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], nx.kbase, m0_next + i * 4096);
-            else dma16(lp.voff_i[i], nx.vbase, m0_next + kTileBytes + i * 4096);
-        }
-        if constexpr (slot >= 64 && TO == kSlots) {
+        if constexpr (slot >= 60 && slot < 68 && TO == kSlots) {
             // the chunk's own LDS stage is not read any more: the read addresses move to the other stage (stage_delta =
             // +- one stage), then the next chunk's first K fragments are fetched (also when there is no next chunk: the
             // address is a valid LDS address)
-            rd.k_addr[slot - 64] += stage_delta;
-            if constexpr (slot < 68) rd.v_addr[slot - 64] += stage_delta;
-            fr.kf0[slot - 64] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 64]);
+            rd.k_addr[slot - 60] += stage_delta;
+            if constexpr (slot < 64) rd.v_addr[slot - 60] += stage_delta;
+            fr.kf0[slot - 60] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 60]);
         }
-        // ---- one exponential; the second of a pair is followed by the pack of the two ----
-        if constexpr (!kSkip && exp_at(slot).valid) {
+        // ---- one exponential; the slot after a pair's second exponential packs the two (not the same slot: the
+        // instruction after a transcendental may not read its result, and the wait state would be one more instruction) ----
+        if constexpr (!kSkip) {
             constexpr ExpSlot e = exp_at(slot);
-            const float ev = __builtin_amdgcn_exp2f(fr.s[e.mb][e.qh][2 * e.gi + e.second]);
-            if constexpr (!e.second) {
-                fr.e_first = ev;
-                asm volatile("" : "+v"(fr.e_first));
-            } else {
-                constexpr int t = e.gi >> 2, i = (2 * e.gi) & 7;
+            constexpr ExpSlot pe = exp_at((slot + kSlots - 1) % kSlots);
+            float ev = 0.f;
+            if constexpr (e.valid) ev = __builtin_amdgcn_exp2f(fr.s[e.mb][e.qh][2 * e.gi + e.second]);
+            if constexpr (pe.valid && pe.second) {
+                constexpr int t = pe.gi >> 2, i = (2 * pe.gi) & 7;
                 v2bf pk;
-                pk[0] = (__bf16)fr.e_first;
-                pk[1] = (__bf16)ev;
-                asm volatile("" : "+v"(pk));      // anchors the pair in this slot of the interleaved stream
-                fr.pf[e.mb][e.qh][t][i] = pk[0];
-                fr.pf[e.mb][e.qh][t][i + 1] = pk[1];
+                pk[0] = (__bf16)fr.e_pair[0];
+                pk[1] = (__bf16)fr.e_pair[1];
+                asm volatile("" : "+v"(pk));      // anchors the pack in this slot of the interleaved stream
+                fr.pf[pe.mb][pe.qh][t][i] = pk[0];
+                fr.pf[pe.mb][pe.qh][t][i + 1] = pk[1];
+            }
+            if constexpr (e.valid) {
+                fr.e_pair[e.second] = ev;
+                asm volatile("" : "+v"(fr.e_pair[e.second]));
+            }
+        }
+        if constexpr (slot >= 56 && slot < 64 && TO == kSlots) {
+            // the barrier has released the stage: one tile load each of the chunk after next
+            constexpr int i = (slot - 56) >> 1;
+            if constexpr (kSkip) {
+                if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], nx.kbase, m0_next + i * 4096);
+                else dma16(lp.voff_i[i], nx.vbase, m0_next + kTileBytes + i * 4096);
+            } else {
+                if constexpr ((slot & 1) == 0) dma16_go(lp.koff_i[i], nx.kbase);
+                else dma16_go(lp.voff_i[i], nx.vbase);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -287,6 +323,13 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
 // normaliser (the compiler's own matrix instructions here: outside the hand-scheduled loop it looks after the wait
 // states between matrix instructions and their neighbours).
 __device__ __forceinline__ void finish_pending(State& st, Frags& fr) {
+    {   // the pair whose second exponential was taken in the last slot: values 6, 7 of the first fragment
+        v2bf pk;
+        pk[0] = (__bf16)fr.e_pair[0];
+        pk[1] = (__bf16)fr.e_pair[1];
+        fr.pf[1][1][0][6] = pk[0];
+        fr.pf[1][1][0][7] = pk[1];
+    }
 #pragma unroll
     for (int gi = 4; gi < 8; ++gi) {
         v2bf pk;
@@ -488,7 +531,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
                     for (int i = 0; i < 8; ++i) fr.vf[1][t][db][i] = (__bf16)0.f;
             }
-            fr.e_first = 0.f;
+            fr.e_pair[0] = fr.e_pair[1] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) fr.kf0[ks] = *(lds_v8)(uintptr_t)(rd.k_addr[ks]);
             // Loop invariant at the top of a chunk: its tiles are complete in LDS for every wave, the K fragments of
@@ -505,24 +548,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                 const bool refill = (nx.c2 >> 1) >= wbase + 64;
                 // a wavefront that sits the chunk out leaves the tile it has in flight as it is: the next chunk it
                 // takes part in (or the code after the loop) completes it
-                if (own_cur) run_slots<0, 27, false>(rd, 0, qf, st, fr, lp, nx, 0);
-                if (refill) {
-                    wbase += 64;
-                    win = gl[min(wbase + lane, cnt - 1)];
-                    asm volatile("" : "+v"(win));
-                }
-                nx.win = win;
-                if (own_cur) {
-                    run_slots<27, kBarrierSlot, false>(rd, 0, qf, st, fr, lp, nx, 0);
-                } else {
-                    next_step<0>(nx); next_step<1>(nx); next_step<2>(nx); next_step<3>(nx); next_step<4>(nx);
-                }
-                DR_WAIT_VMCNT0();
-                DR_BARRIER();
-                __builtin_amdgcn_sched_barrier(0);
                 const uint32_t m0n = lp.m0_k + stage * kStageBytes;
-                if (own_cur) run_slots<kBarrierSlot, kSlots, false>(rd, stage ? -kStageBytes : kStageBytes, qf, st, fr, lp, nx, m0n);
-                else run_slots<kBarrierSlot, kSlots, true>(rd, stage ? -kStageBytes : kStageBytes, qf, st, fr, lp, nx, m0n);
+                const int stage_delta = stage ? -kStageBytes : kStageBytes;
+                auto refill_window = [&]() {
+                    if (refill) {
+                        wbase += 64;
+                        win = gl[min(wbase + lane, cnt - 1)];
+                        asm volatile("" : "+v"(win));
+                    }
+                    nx.win = win;
+                };
+                if (own_cur) {
+                    run_slots<0, 27, false>(rd, 0, qf, st, fr, lp, nx, 0);
+                    refill_window();
+                    run_slots<27, kBarrierSlot, false>(rd, 0, qf, st, fr, lp, nx, 0);
+                    DR_WAIT_VMCNT0();
+                    DR_BARRIER();
+                    __builtin_amdgcn_sched_barrier(0);
+                    run_slots<kBarrierSlot, kSlots, false>(rd, stage_delta, qf, st, fr, lp, nx, m0n);
+                } else {
+                    refill_window();
+                    next_step<0>(nx); next_step<1>(nx); next_step<2>(nx); next_step<3>(nx); next_step<4>(nx);
+                    DR_WAIT_VMCNT0();
+                    DR_BARRIER();
+                    __builtin_amdgcn_sched_barrier(0);
+                    run_slots<kBarrierSlot, kSlots, true>(rd, stage_delta, qf, st, fr, lp, nx, m0n);
+                }
                 DR_PIN_O();
                 own_cur = own_nxt;
                 own_nxt = nx.own;
