@@ -14,12 +14,14 @@
 // per cent longer than a row.
 //
 // With a single wavefront per SIMD nothing else hides a wavefront's own latencies, so the chunk is software-pipelined
-// by hand: 64 matrix-instruction slots per chunk with one exponential, and at most a few other instructions, in the
+// by hand: 72 matrix-instruction slots per chunk with at most one exponential and a few other instructions in the
 // shadow of each (see the schedule below); the exponentials of a chunk's last logit tile and its O += V P run under
-// the first slots of the next chunk.  v_dot2c_f32_bf16 is not used for the normaliser: it serialises with the matrix
-// pipe (a wavefront's matrix instruction + two exponentials + pack + dot takes 77 cycles, with two adds 49).
+// the first slots of the next chunk.  Every instruction beside the matrix instruction costs a lone wavefront issue
+// time even in that shadow (about 1.8 cycles of the slot each, scalar instructions and waits included), so the loop
+// is kept as short as it can be: the normaliser is summed by the matrix pipe, waits are placed by hand once per
+// batch of LDS reads, and what a chunk needs to know about the chunk after next is worked out inside slots.
 // A lone wavefront also pays for every branch in full (a not-taken branch between two matrix instructions costs it
-// 9 to 26 cycles), so the 64 slots of a chunk are straight-line code without any masking: the pipelined loop takes
+// 9 to 26 cycles), so the 72 slots of a chunk are straight-line code without any masking: the pipelined loop takes
 // full 64-key chunks only, and the tile loads of the chunk after next are always issued (past the end of the list
 // they re-read the last window into the stage nobody reads).  The one chunk of a sequence that can be partial (in
 // its last key block) is taken before the loop, by plain code, from a 64-row window moved back to end at the last
@@ -33,7 +35,8 @@
 // flagged and taken again by k_attn_mfma's second pass, which moves a reference and scales in fp32.  Below the
 // limit nothing overflows (fp32 and bf16 share one exponent range, so large or small probabilities lose no
 // precision), the logit accumulation starts from the constant 0, and the accumulators, which are out of the vector
-// ALU's reach, never need rescaling.  The normaliser sums the probabilities as rounded to bf16.
+// ALU's reach, never need rescaling.  The normaliser sums the probabilities as rounded to bf16 (by one more matrix
+// instruction per P^T fragment, with an all-ones A operand).
 #include "attn_mfma_common.h"
 #include "dr_internal.h"
 
