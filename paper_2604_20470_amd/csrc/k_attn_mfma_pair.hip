@@ -7,7 +7,7 @@
 // per workgroup (k_attn_mfma) every K / V fragment read from LDS feeds two matrix instructions instead of one, and
 // every K / V tile fetched from L2 serves 256 queries instead of 128: the kernel runs at the device's power limit,
 // so fewer joules per chunk is what buys time.
-// The workgroup walks the ascending UNION of the two CSR rows (formed beforehand by k_pair_union: key block in the
+// The workgroup walks the ascending UNION of the two CSR rows (formed beforehand by k_group_union: key block in the
 // low 28 bits of an entry, the rows that list it in bits 28-29); a wavefront whose query block does not list a key
 // block runs the chunk with every logit masked.  Neighbouring query blocks share most of their key blocks (the
 // never-pruned zone of a frame, and, for score-based selection, similar pooled scores), so the union is only a few
@@ -235,13 +235,16 @@ __device__ __forceinline__ void dma16_go(uint32_t voff, uint64_t base) {
 // to have had time to arrive, one wait replaces the one per fragment the compiler would otherwise put before every use.
 #define DR_WAIT_LGKM(n) __builtin_amdgcn_s_waitcnt(0xC07F | ((n) << 8))
 
-// Slots [FROM, TO) of the chunk whose tiles sit at LDS addresses rd (stage offset already added).  Slots 56..63 move rd
-// to the other stage, read the next chunk's first K fragments from there and issue one tile load each of the window at
-// kbase / vbase into the stage at m0_next; with kSkip they do only that (a wavefront that sits the chunk out).
-template <int FROM, int TO, bool kSkip>
-__device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v8bf (&qf)[2][8], State& st, Frags& fr,
-                                          const LoadPlan& lp, Next& nx, uint32_t m0_next) {
-    constexpr uint32_t kV = kTileBytes;
+// Slots [FROM, TO) of the chunk whose tiles sit in LDS stage STAGE.  rd holds the stage-0 addresses and never
+// changes: the stage is a compile-time offset of every read (the chunk loop is unrolled over the two stages).  Slots
+// 56..63 issue one tile load each of the window at nx.kbase / nx.vbase into this stage, which the barrier before them
+// has released; slots 60..67 read the next chunk's first K fragments from the other stage; with kSkip a wavefront
+// does only that (it sits the chunk out).
+template <int FROM, int TO, bool kSkip, int STAGE>
+__device__ __forceinline__ void run_slots(const ReadPlan& rd, const v8bf (&qf)[2][8], State& st, Frags& fr,
+                                          const LoadPlan& lp, Next& nx) {
+    constexpr uint32_t kS = STAGE * kStageBytes, kV = kS + kTileBytes;
+    const uint32_t m0_next = lp.m0_k;
     static_for<FROM, TO>([&](auto slot_c) {
         constexpr int slot = decltype(slot_c)::value;
         constexpr MfmaSlot m = mfma_at(slot);
@@ -257,7 +260,7 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
         }
         if constexpr (!kSkip && slot >= 56 && slot < 64 && TO == kSlots) {
             constexpr int i = (slot - 56) >> 1;
-            set_m0<((slot & 1) ? kTileBytes : 0) + i * 4096>(m0_next);
+            set_m0<kS + ((slot & 1) ? kTileBytes : 0) + i * 4096>(m0_next);
         }
         if constexpr (kSkip) {
         } else if constexpr (m.kind == 0) {
@@ -270,7 +273,7 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
             mfma_pv(st.lacc[m.qh], st.ones, fr.pf[m.mb][m.qh][m.idx]);
         }
         // ---- LDS reads ----
-        if constexpr (slot >= 10 && slot < 18) fr.kf1[slot - 10] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 10] + 32 * kRowBytes);
+        if constexpr (slot >= 10 && slot < 18) fr.kf1[slot - 10] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 10] + kS + 32 * kRowBytes);
         if constexpr ((slot >= 18 && slot < 26) || (slot >= 44 && slot < 52)) {
             constexpr int mb = slot >= 44, f = mb ? slot - 44 : slot - 18, t = f >> 2, db = f & 3;
             union { struct { v4s a, b; } s2; v8bf v; } u;
@@ -279,12 +282,9 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
             fr.vf[mb][t][db] = u.v;
         }
         if constexpr (slot >= 60 && slot < 68 && TO == kSlots) {
-            // the chunk's own LDS stage is not read any more: the read addresses move to the other stage (stage_delta =
-            // +- one stage), then the next chunk's first K fragments are fetched (also when there is no next chunk: the
-            // address is a valid LDS address)
-            rd.k_addr[slot - 60] += stage_delta;
-            if constexpr (slot < 64) rd.v_addr[slot - 60] += stage_delta;
-            fr.kf0[slot - 60] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 60]);
+            // the next chunk's first K fragments, from the other stage (also when there is no next chunk: the address is
+            // a valid LDS address)
+            fr.kf0[slot - 60] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 60] + (1 - STAGE) * kStageBytes);
         }
         // ---- one exponential; the slot after a pair's second exponential packs the two (not the same slot: the
         // instruction after a transcendental may not read its result, and the wait state would be one more instruction) ----
@@ -311,8 +311,8 @@ __device__ __forceinline__ void run_slots(ReadPlan& rd, int stage_delta, const v
             // the barrier has released the stage: one tile load each of the chunk after next
             constexpr int i = (slot - 56) >> 1;
             if constexpr (kSkip) {
-                if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], nx.kbase, m0_next + i * 4096);
-                else dma16(lp.voff_i[i], nx.vbase, m0_next + kTileBytes + i * 4096);
+                if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], nx.kbase, m0_next + kS + i * 4096);
+                else dma16(lp.voff_i[i], nx.vbase, m0_next + kS + kTileBytes + i * 4096);
             } else {
                 if constexpr ((slot & 1) == 0) dma16_go(lp.koff_i[i], nx.kbase);
                 else dma16_go(lp.voff_i[i], nx.vbase);
@@ -540,48 +540,44 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             // Loop invariant at the top of a chunk: its tiles are complete in LDS for every wave, the K fragments of
             // its first key half are on their way to registers, and the loads of the following chunk have been issued.
             asm volatile("" : "+v"(fr.s[1][1]));
-            int stage = 0;                      // LDS stage of the chunk being consumed
             bool own_cur = d0.own, own_nxt = d1.own;
             Next nx;
             nx.Sb = a.Sb; nx.N = N; nx.grp = grp; nx.row_bytes = (uint32_t)row_bytes; nx.Kh = Kh; nx.Vh = Vh;
-            for (int c = 0; c < n_chunks; ++c) {
-                DR_PIN_O();
-                // the chunk after next (past the end of the list: the last chunk again, into the stage nobody reads)
-                nx.c2 = min(c + 2, n_chunks - 1);
-                const bool refill = (nx.c2 >> 1) >= wbase + 64;
-                // a wavefront that sits the chunk out leaves the tile it has in flight as it is: the next chunk it
-                // takes part in (or the code after the loop) completes it
-                const uint32_t m0n = lp.m0_k + stage * kStageBytes;
-                const int stage_delta = stage ? -kStageBytes : kStageBytes;
-                auto refill_window = [&]() {
-                    if (refill) {
-                        wbase += 64;
-                        win = gl[min(wbase + lane, cnt - 1)];
-                        asm volatile("" : "+v"(win));
-                    }
-                    nx.win = win;
-                };
-                if (own_cur) {
-                    run_slots<0, 27, false>(rd, 0, qf, st, fr, lp, nx, 0);
-                    refill_window();
-                    run_slots<27, kBarrierSlot, false>(rd, 0, qf, st, fr, lp, nx, 0);
-                    DR_WAIT_VMCNT0();
-                    DR_BARRIER();
-                    __builtin_amdgcn_sched_barrier(0);
-                    run_slots<kBarrierSlot, kSlots, false>(rd, stage_delta, qf, st, fr, lp, nx, m0n);
-                } else {
-                    refill_window();
-                    next_step<0>(nx); next_step<1>(nx); next_step<2>(nx); next_step<3>(nx); next_step<4>(nx);
-                    DR_WAIT_VMCNT0();
-                    DR_BARRIER();
-                    __builtin_amdgcn_sched_barrier(0);
-                    run_slots<kBarrierSlot, kSlots, true>(rd, stage_delta, qf, st, fr, lp, nx, m0n);
-                }
-                DR_PIN_O();
-                own_cur = own_nxt;
-                own_nxt = nx.own;
-                stage ^= 1;
+            // The loop takes two chunks per turn, one per LDS stage, so that the stage is a compile-time offset of every
+            // read; an odd count is made even by a last chunk that every wavefront sits out.
+            const int n_even = (n_chunks + 1) & ~1;
+#define DR_CHUNK(STAGE, C)                                                                                              \
+            {                                                                                                           \
+                DR_PIN_O();                                                                                             \
+                nx.c2 = min((C) + 2, n_chunks - 1);                                                                     \
+                const bool refill = (nx.c2 >> 1) >= wbase + 64;                                                         \
+                if (own_cur) {                                                                                          \
+                    run_slots<0, 27, false, STAGE>(rd, qf, st, fr, lp, nx);                                             \
+                    if (refill) { wbase += 64; win = gl[min(wbase + lane, cnt - 1)]; asm volatile("" : "+v"(win)); }   \
+                    nx.win = win;                                                                                       \
+                    run_slots<27, kBarrierSlot, false, STAGE>(rd, qf, st, fr, lp, nx);                                  \
+                    DR_WAIT_VMCNT0();                                                                                   \
+                    DR_BARRIER();                                                                                       \
+                    __builtin_amdgcn_sched_barrier(0);                                                                  \
+                    run_slots<kBarrierSlot, kSlots, false, STAGE>(rd, qf, st, fr, lp, nx);                              \
+                } else {                                                                                                \
+                    if (refill) { wbase += 64; win = gl[min(wbase + lane, cnt - 1)]; asm volatile("" : "+v"(win)); }   \
+                    nx.win = win;                                                                                       \
+                    next_step<0>(nx); next_step<1>(nx); next_step<2>(nx); next_step<3>(nx); next_step<4>(nx);           \
+                    DR_WAIT_VMCNT0();                                                                                   \
+                    DR_BARRIER();                                                                                       \
+                    __builtin_amdgcn_sched_barrier(0);                                                                  \
+                    run_slots<kBarrierSlot, kSlots, true, STAGE>(rd, qf, st, fr, lp, nx);                               \
+                }                                                                                                       \
+                DR_PIN_O();                                                                                             \
+                own_cur = own_nxt && (C) + 1 < n_chunks;                                                                \
+                own_nxt = nx.own;                                                                                       \
             }
+            for (int c = 0; c < n_even; c += 2) {
+                DR_CHUNK(0, c)
+                DR_CHUNK(1, c + 1)
+            }
+#undef DR_CHUNK
             finish_pending(st, fr);
         }
         DR_WAIT_VMCNT0();          // the loads issued by the last chunks write LDS: none may outlive the workgroup
