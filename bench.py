@@ -147,7 +147,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=6)          # the shader clock settles over the first ~5 attention launches of a train
     ap.add_argument("--config", default="cfg4")
     ap.add_argument("--heads", type=int, default=0, help="use only the first H heads (0 = the workload's own count)")
     ap.add_argument("--block-size", type=int, default=0, help="override the workload's block size Bs (32, 64 or 128)")
