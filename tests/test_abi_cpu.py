@@ -62,3 +62,34 @@ def test_product_does_not_import_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.replace("no CPU fallback", ""), f
+
+
+def test_hand_scheduled_attention_kernel_compiles_without_spills_or_accumulator_copies():
+    """k_attn_mfma_pair issues its matrix instructions through inline assembly, so the compiler neither knows their
+    latency nor may move an accumulator while one of them still writes it.  A register allocation that spills, or that
+    copies accumulation registers inside the chunk loop, computes garbage without any error: check the compiler's own
+    report and the loop's code (cross-compiled here, nothing runs)."""
+    import shutil
+    import subprocess
+    import tempfile
+    from paper_2604_20470_amd import build as b
+    if not (os.path.exists(b.HIPCC) or shutil.which(b.HIPCC)):
+        pytest.skip("no hipcc")
+    src = os.path.join(b.CSRC, "k_attn_mfma_pair.hip")
+    with tempfile.TemporaryDirectory() as tmp:
+        asm = os.path.join(tmp, "pair.s")
+        r = subprocess.run([b.HIPCC, *[f for f in b.FLAGS if f != "-fPIC"], "-Rpass-analysis=kernel-resource-usage", "-S",
+                            "--cuda-device-only", src, "-o", asm], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-2000:]
+        report = r.stderr[r.stderr.index("k_attn_mfma_pair"):]
+        field = lambda name: int(re.search(name + r": (\d+)", report).group(1))
+        assert field("VGPRs Spill") == 0 and field("SGPRs Spill") == 0
+        assert field("VGPRs") <= 256 and field("AGPRs") <= 256
+        lines = open(asm).read().splitlines()
+    start = next(i for i, l in enumerate(lines) if "Loop Header" in l)
+    label = lines[start].split(":")[0]
+    end = max(i for i, l in enumerate(lines) if re.search(r"s_c?branch\S*\s+" + re.escape(label) + r"\s*$", l))
+    loop = lines[start:end]
+    assert sum("v_mfma_f32_32x32x16_bf16" in l for l in loop) == 144          # two chunks of 72 slots
+    assert not any("v_accvgpr" in l for l in loop)
+    assert not any("scratch_" in l or "buffer_store" in l for l in loop)
