@@ -549,20 +549,20 @@ dr_status attn_prepare(dr_ctx* ctx, const dr_shape* shape, const void* Q, const 
     return DR_OK;
 }
 
-// Block size 128: pairs of adjacent query blocks walk the union of their two rows; rows the pair kernel flags are
-// taken again by the single-row kernel's second pass.
+// Block sizes 128 and 64: the 256 queries of two (four) adjacent query blocks walk the union of their rows, one
+// wavefront per SIMD; rows that kernel flags are taken again by the second pass of the kernels with one 128-row group
+// per workgroup.
 bool attn_wants_pairs(const dr_ctx* ctx, const AttnArgs& a) {
-    return ctx->attn_pairs && attn_mfma_supported(a) && a.td.N >= 64 && a.Sb < (1 << 28);
+    return ctx->attn_pairs && a.bf16 && a.td.d == 128 && (a.Bs == 128 || a.Bs == 64) && a.td.N >= 64 && a.Sb < (1 << 28);
 }
 
 dr_status attn_launch(dr_ctx* ctx, const AttnArgs& a, bool pairs, hipStream_t s) {
-    if (attn_mfma_supported(a)) {
-        if (pairs && attn_mfma_pair_supported(a)) {
-            DR_HIP(ctx, launch_attn_mfma_pair(a, s));
-            DR_HIP(ctx, launch_attn_mfma_second_pass(a, s));
-        } else {
-            DR_HIP(ctx, launch_attn_mfma(a, s));
-        }
+    if (pairs && attn_mfma_pair_supported(a)) {
+        DR_HIP(ctx, launch_attn_mfma_pair(a, s));
+        if (a.Bs == 128) DR_HIP(ctx, launch_attn_mfma_second_pass(a, s));
+        else DR_HIP(ctx, launch_attn_mfma_small_second_pass(a, s));
+    } else if (attn_mfma_supported(a)) {
+        DR_HIP(ctx, launch_attn_mfma(a, s));
     } else if (attn_mfma_small_supported(a)) {
         DR_HIP(ctx, launch_attn_mfma_small(a, s));
     } else {

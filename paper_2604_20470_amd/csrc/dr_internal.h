@@ -113,6 +113,7 @@ bool attn_mfma_pair_supported(const AttnArgs& a);
 hipError_t launch_group_union(int L, const AttnArgs& a, hipStream_t s);
 // bf16 storage, d = 128, Bs = 32 or 64: MFMA path that walks the union of the CSR rows of a 128-query group.
 hipError_t launch_attn_mfma_small(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_mfma_small_second_pass(const AttnArgs& a, hipStream_t s);
 bool attn_mfma_small_supported(const AttnArgs& a);
 
 // ---- evaluation aid: the proxy objective of the offline search (App. C, Eq. 22) ----------------------

@@ -48,7 +48,8 @@ namespace {
 
 using namespace mfma;
 
-constexpr int kD = 128, kBs = 128;
+constexpr int kD = 128;
+constexpr int kRowsPerItem = 256;                    // queries of a workgroup: 256 / Bs adjacent query blocks
 constexpr int kWaves = 4, kThreads = kWaves * 64;
 constexpr int kChunkKeys = 64;
 constexpr int kRowBytes = kD * 2;                    // 256
@@ -198,7 +199,7 @@ __device__ __forceinline__ void mask_front(v16f& s, int mb, int half, int lo) {
 // shadow of slots 28..32: between two slots the same instructions would leave the matrix pipe idle (a lone wavefront
 // issues one instruction every four to five cycles, whatever its kind).
 struct Next {
-    int c2, win, Sb, N, grp;          // in: chunk index, the register window over the merged list, limits, the wave's query block
+    int c2, win, Sb, N, grp;          // in: chunk index, the register window over the merged list, limits, the wave's owner bit
     uint32_t row_bytes;
     const char *Kh, *Vh;
     uint32_t e;                       // the list entry
@@ -206,13 +207,14 @@ struct Next {
     uint64_t off, kbase, vbase;
     bool own;                         // the wave's query block lists the key block
 };
-template <int K>
+template <int K, int BS>
 __device__ __forceinline__ void next_step(Next& nx) {
-    if constexpr (K == 0) nx.e = (uint32_t)__builtin_amdgcn_readlane(nx.win, (nx.c2 >> 1) & 63);
+    constexpr int kSh = BS == 128 ? 1 : 0;      // chunks per list entry, as a shift
+    if constexpr (K == 0) nx.e = (uint32_t)__builtin_amdgcn_readlane(nx.win, (nx.c2 >> kSh) & 63);
     if constexpr (K == 1) {
         // (the clamp of the key block never acts on a list as k_group_union writes it; it keeps any other list inside K / V)
         const int kb = min((int)(nx.e & 0x0fffffffu), nx.Sb - 1);
-        nx.key0 = min(kb * kBs + (nx.c2 & 1) * kChunkKeys, nx.N - kChunkKeys);
+        nx.key0 = min(kb * BS + (nx.c2 & kSh) * kChunkKeys, nx.N - kChunkKeys);
     }
     if constexpr (K == 2) {
         nx.own = ((nx.e >> (28 + nx.grp)) & 1u) != 0;
@@ -240,7 +242,7 @@ __device__ __forceinline__ void dma16_go(uint32_t voff, uint64_t base) {
 // 56..63 issue one tile load each of the window at nx.kbase / nx.vbase into this stage, which the barrier before them
 // has released; slots 60..67 read the next chunk's first K fragments from the other stage; with kSkip a wavefront
 // does only that (it sits the chunk out).
-template <int FROM, int TO, bool kSkip, int STAGE>
+template <int FROM, int TO, bool kSkip, int STAGE, int BS>
 __device__ __forceinline__ void run_slots(const ReadPlan& rd, const v8bf (&qf)[2][8], State& st, Frags& fr,
                                           const LoadPlan& lp, Next& nx) {
     constexpr uint32_t kS = STAGE * kStageBytes, kV = kS + kTileBytes;
@@ -248,7 +250,7 @@ __device__ __forceinline__ void run_slots(const ReadPlan& rd, const v8bf (&qf)[2
     static_for<FROM, TO>([&](auto slot_c) {
         constexpr int slot = decltype(slot_c)::value;
         constexpr MfmaSlot m = mfma_at(slot);
-        if constexpr (!kSkip && slot >= 28 && slot < 33) next_step<slot - 28>(nx);
+        if constexpr (!kSkip && slot >= 28 && slot < 33) next_step<slot - 28, BS>(nx);
         if constexpr (!kSkip) {
             // K fragments of key half 0 (read in slots 60..67 of the previous chunk); of key half 1 (slots 10..17: at most
             // the 16 V^T reads behind them are still out); V^T of key half 0 (18..25); of key half 1 (44..51: only
@@ -391,22 +393,26 @@ __device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_o
         }
 }
 
-// grid: (ceil(Sb / 2) * H * B) in one dimension, remapped so that one XCD walks a contiguous run of items.
-// One workgroup = 4 waves of 64 queries = two adjacent query blocks (waves 0-1: block 2p, waves 2-3: block 2p + 1).
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_pair(AttnArgs a) {
+// grid: (ceil(Sb / kL) * H * B) in one dimension, remapped so that one XCD walks a contiguous run of items.
+// One workgroup = 4 waves of 64 queries = kL adjacent query blocks (BS = 128: waves 0-1 block 2p, waves 2-3 block
+// 2p + 1; BS = 64: wave w block 4p + w).
+template <int BS>
+__device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
+    constexpr int kL = kRowsPerItem / BS;       // query blocks per workgroup: 2 (waves 0-1, 2-3) or 4 (one per wave)
+    constexpr int kSh = BS == 128 ? 1 : 0;      // chunks per list entry, as a shift
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int half = lane >> 5, l32 = lane & 31;
     constexpr int kXcds = 8;
-    const int n_pairs = (a.Sb + 1) / 2;
+    const int n_pairs = (a.Sb + kL - 1) / kL;
     const int total_items = n_pairs * a.td.H * a.td.B;
     const int per_xcd = (total_items + kXcds - 1) / kXcds;
     const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     if (item >= total_items) return;
     const int pair = item % n_pairs, h = (item / n_pairs) % a.td.H, b = item / (n_pairs * a.td.H);
-    const int grp = wave >> 1;
-    const bool has_rows = 2 * pair + grp < a.Sb;
-    const int qb = min(2 * pair + grp, a.Sb - 1);
+    const int grp = BS == 128 ? wave >> 1 : wave;
+    const bool has_rows = kL * pair + grp < a.Sb;
+    const int qb = min(kL * pair + grp, a.Sb - 1);
     const int N = a.td.N;
     const int64_t row_bytes = a.td.stride_n * 2;
     const int64_t head_off = ((int64_t)b * a.td.stride_b + (int64_t)h * a.td.stride_h) * 2;
@@ -417,12 +423,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int64_t mask_id = (int64_t)b * a.mask_heads + mh;
     const int32_t* rp = a.rowptr + mask_id * (a.Sb + 1);
     // the pair's merged list sits at the colidx offset of its first row (as k_group_union writes it)
-    const int64_t goff = min(max((int64_t)__builtin_amdgcn_readfirstlane(rp[2 * pair]), (int64_t)0), a.colidx_stride);
+    const int64_t goff = min(max((int64_t)__builtin_amdgcn_readfirstlane(rp[kL * pair]), (int64_t)0), a.colidx_stride);
     const int32_t* gl = a.gcol + mask_id * a.colidx_stride + goff;
     const int cnt = __builtin_amdgcn_readfirstlane(a.gcount[mask_id * n_pairs + pair]);
 
     const float cs = kExpScale;
-    const int q_wave0 = qb * kBs + (wave & 1) * 64;
+    const int q_wave0 = BS == 128 ? qb * 128 + (wave & 1) * 64 : qb * 64;
     v8bf qf[2][8];
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
@@ -481,7 +487,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     // and, if n_last is no multiple of 64, one partial chunk that is taken first, from the window of the sequence's
     // last 64 rows (its leading 64 - n_last % 64 rows masked).  The list is ascending, so only its last entry can be
     // that block. ----
-    const int n_last = N - (a.Sb - 1) * kBs;
+    const int n_last = N - (a.Sb - 1) * BS;
     const int part_keys = n_last % kChunkKeys;
     int wbase = 0;
     int win = (cnt > 0) ? gl[min(lane, cnt - 1)] : 0;
@@ -496,15 +502,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     asm volatile("" : "+v"(win));
     const uint32_t e_last_s = __builtin_amdgcn_readfirstlane(e_last);
     const bool has_last = cnt > 0 && (int)(e_last_s & 0x0fffffffu) >= a.Sb - 1;
-    const int n_chunks = 2 * cnt - (has_last ? 2 - n_last / kChunkKeys : 0);     // full chunks, in list order
+    const int n_chunks = (cnt << kSh) - (has_last ? (1 << kSh) - n_last / kChunkKeys : 0);     // full chunks, in list order
     const bool has_part = has_last && part_keys != 0;
     const bool own_part = ((e_last_s >> (28 + grp)) & 1u) != 0;
     struct Desc { int key0; bool own; };
     auto describe = [&](int c) -> Desc {          // c < n_chunks, its entry inside the register window
-        const uint32_t e = (uint32_t)__builtin_amdgcn_readlane(win, (c >> 1) & 63);
+        const uint32_t e = (uint32_t)__builtin_amdgcn_readlane(win, (c >> kSh) & 63);
         const int kb = min((int)(e & 0x0fffffffu), a.Sb - 1);
         // (the clamp never acts on a list as k_group_union writes it; it keeps any other list inside K / V)
-        return Desc{min(kb * kBs + (c & 1) * kChunkKeys, N - kChunkKeys), ((e >> (28 + grp)) & 1u) != 0};
+        return Desc{min(kb * BS + (c & kSh) * kChunkKeys, N - kChunkKeys), ((e >> (28 + grp)) & 1u) != 0};
     };
 
     if (n_chunks > 0 || has_part) {
@@ -550,33 +556,35 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             {                                                                                                           \
                 DR_PIN_O();                                                                                             \
                 nx.c2 = min((C) + 2, n_chunks - 1);                                                                     \
-                const bool refill = (nx.c2 >> 1) >= wbase + 64;                                                         \
+                const bool refill = (nx.c2 >> kSh) >= wbase + 64;                                                       \
                 if (own_cur) {                                                                                          \
-                    run_slots<0, 27, false, STAGE>(rd, qf, st, fr, lp, nx);                                             \
+                    run_slots<0, 27, false, STAGE, BS>(rd, qf, st, fr, lp, nx);                                             \
                     if (refill) { wbase += 64; win = gl[min(wbase + lane, cnt - 1)]; asm volatile("" : "+v"(win)); }   \
                     nx.win = win;                                                                                       \
-                    run_slots<27, kBarrierSlot, false, STAGE>(rd, qf, st, fr, lp, nx);                                  \
+                    run_slots<27, kBarrierSlot, false, STAGE, BS>(rd, qf, st, fr, lp, nx);                                  \
                     DR_WAIT_VMCNT0();                                                                                   \
                     DR_BARRIER();                                                                                       \
                     __builtin_amdgcn_sched_barrier(0);                                                                  \
-                    run_slots<kBarrierSlot, kSlots, false, STAGE>(rd, qf, st, fr, lp, nx);                              \
+                    run_slots<kBarrierSlot, kSlots, false, STAGE, BS>(rd, qf, st, fr, lp, nx);                              \
                 } else {                                                                                                \
                     if (refill) { wbase += 64; win = gl[min(wbase + lane, cnt - 1)]; asm volatile("" : "+v"(win)); }   \
                     nx.win = win;                                                                                       \
-                    next_step<0>(nx); next_step<1>(nx); next_step<2>(nx); next_step<3>(nx); next_step<4>(nx);           \
+                    next_step<0, BS>(nx); next_step<1, BS>(nx); next_step<2, BS>(nx); next_step<3, BS>(nx); next_step<4, BS>(nx);           \
                     DR_WAIT_VMCNT0();                                                                                   \
                     DR_BARRIER();                                                                                       \
                     __builtin_amdgcn_sched_barrier(0);                                                                  \
-                    run_slots<kBarrierSlot, kSlots, true, STAGE>(rd, qf, st, fr, lp, nx);                               \
+                    run_slots<kBarrierSlot, kSlots, true, STAGE, BS>(rd, qf, st, fr, lp, nx);                               \
                 }                                                                                                       \
                 DR_PIN_O();                                                                                             \
                 own_cur = own_nxt && (C) + 1 < n_chunks;                                                                \
                 own_nxt = nx.own;                                                                                       \
             }
-            for (int c = 0; c < n_even; c += 2) {
-                DR_CHUNK(0, c)
+            asm volatile("; chunk loop begin");      // (markers for the check of the generated code: nothing
+            for (int c = 0; c < n_even; c += 2) {    // between them may touch an accumulation register except the
+                DR_CHUNK(0, c)                        // matrix instructions themselves)
                 DR_CHUNK(1, c + 1)
             }
+            asm volatile("; chunk loop end");
 #undef DR_CHUNK
             finish_pending(st, fr);
         }
@@ -611,30 +619,42 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             if (listed && !(l >= kSumMin && l <= kSumMax && fabsf(__log2f(l)) <= kExactLimit)) out_of_range = true;
         }
     }
-    if (a.flags && has_rows) {      // two words per wave: it covers the rows of two 32-row waves of k_attn_mfma
-        const int any = __any(out_of_range) ? 1 : 0;
-        const int64_t base = (((int64_t)b * a.td.H + h) * a.Sb + qb) * 4 + (wave & 1) * 2;
+    // Two flag words per wave: it covers the rows of two 32-row waves of the kernels that make the second pass; they are
+    // indexed by 128-row group, four words each.  A wave whose query block lies past the end of the sequence still
+    // clears its words when its group exists (block size 64, odd block count): the second pass reads all four.
+    const int groups128 = (N + 127) / 128;
+    const int q0_own = (kL * pair + grp) * BS + (BS == 128 ? (wave & 1) * 64 : 0);      // not clamped
+    if (a.flags && (q0_own >> 7) < groups128) {
+        const int any = (has_rows && __any(out_of_range)) ? 1 : 0;
+        const int64_t base = (((int64_t)b * a.td.H + h) * groups128 + (q0_own >> 7)) * 4 + ((q0_own >> 6) & 1) * 2;
         if (lane < 2) a.flags[base + lane] = any;
     }
 }
+
+// Block size 128: two query blocks per workgroup, an entry of the merged list is two chunks.  Block size 64: four
+// query blocks, one per wavefront, an entry is one chunk; the same 256 queries and the same code otherwise.
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_pair(AttnArgs a) { attn_pair_body<128>(a); }
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_quad(AttnArgs a) { attn_pair_body<64>(a); }
 
 }  // namespace
 
 bool attn_mfma_pair_supported(const AttnArgs& a) {
     // every chunk is a full 64-row window: the sequence must hold one; the 32-bit per-lane offsets must cover it
-    return a.bf16 && a.td.d == kD && a.Bs == kBs && a.td.N >= kChunkKeys && a.Sb < (1 << 28) &&
+    return a.bf16 && a.td.d == kD && (a.Bs == 128 || a.Bs == 64) && a.td.N >= kChunkKeys && a.Sb < (1 << 28) &&
            a.td.stride_n * 2 * kChunkKeys < (1ll << 31) && a.gcol && a.gcount && a.flags;
 }
 
 hipError_t launch_attn_mfma_pair(const AttnArgs& a, hipStream_t s) {
     if (!attn_mfma_pair_supported(a)) return hipErrorNotSupported;
-    hipError_t e = launch_group_union(2, a, s);
+    const int L = kRowsPerItem / a.Bs;
+    hipError_t e = launch_group_union(L, a, s);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_attn_mfma_pair), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    auto kern = a.Bs == 128 ? k_attn_mfma_pair : k_attn_mfma_quad;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    const int total = ((a.Sb + 1) / 2) * a.td.H * a.td.B;
+    const int total = ((a.Sb + L - 1) / L) * a.td.H * a.td.B;
     const int grid = (total + 7) / 8 * 8;          // every XCD gets the same number of slots
-    hipLaunchKernelGGL(k_attn_mfma_pair, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, s, a);
     return hipGetLastError();
 }
 

@@ -552,6 +552,21 @@ bool attn_mfma_small_supported(const AttnArgs& a) {
     return a.bf16 && a.td.d == kD && (a.Bs == 32 || a.Bs == 64) && a.td.stride_n * 2 * kChunkKeys < (1ll << 31);
 }
 
+// The second pass alone (the 128-row groups flagged in a.flags, with fp32 exponent scaling), behind a fast pass that
+// another kernel has made: the merged lists of the groups are rebuilt first, a.gcol / a.gcount may hold others.
+hipError_t launch_attn_mfma_small_second_pass(const AttnArgs& a, hipStream_t s) {
+    if (!attn_mfma_small_supported(a) || !a.flags) return hipErrorNotSupported;
+    hipError_t e = launch_group_union(kRowsPerGroup / a.Bs, a, s);
+    if (e != hipSuccess) return e;
+    auto kern = a.Bs == 32 ? k_attn_mfma_bs32_exact : k_attn_mfma_bs64_exact;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    const int groups = (a.td.N + kRowsPerGroup - 1) / kRowsPerGroup;
+    const int total = groups * a.td.H * a.td.B;
+    hipLaunchKernelGGL(kern, dim3((total + 7) / 8 * 8), dim3(kThreads), kLdsBytes, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_mfma_small(const AttnArgs& a, hipStream_t s) {
     if (!attn_mfma_small_supported(a)) return hipErrorNotSupported;
     return a.Bs == 32 ? launch_small(k_attn_mfma_bs32, k_attn_mfma_bs32_exact, a, s)

@@ -81,15 +81,18 @@ def test_hand_scheduled_attention_kernel_compiles_without_spills_or_accumulator_
         r = subprocess.run([b.HIPCC, *[f for f in b.FLAGS if f != "-fPIC"], "-Rpass-analysis=kernel-resource-usage", "-S",
                             "--cuda-device-only", src, "-o", asm], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr[-2000:]
-        report = r.stderr[r.stderr.index("k_attn_mfma_pair"):]
-        field = lambda name: int(re.search(name + r": (\d+)", report).group(1))
-        assert field("VGPRs Spill") == 0 and field("SGPRs Spill") == 0
-        assert field("VGPRs") <= 256 and field("AGPRs") <= 256
+        reports = [blk for blk in r.stderr.split("Function Name:")[1:] if "k_attn_mfma_pair" in blk or "k_attn_mfma_quad" in blk]
+        assert len(reports) == 2                      # block size 128 and block size 64
+        for report in reports:
+            field = lambda name: int(re.search(name + r": (\d+)", report).group(1))
+            assert field("VGPRs Spill") == 0 and field("SGPRs Spill") == 0
+            assert field("VGPRs") <= 256 and field("AGPRs") <= 256
         lines = open(asm).read().splitlines()
-    start = next(i for i, l in enumerate(lines) if "Loop Header" in l)
-    label = lines[start].split(":")[0]
-    end = max(i for i, l in enumerate(lines) if re.search(r"s_c?branch\S*\s+" + re.escape(label) + r"\s*$", l))
-    loop = lines[start:end]
-    assert sum("v_mfma_f32_32x32x16_bf16" in l for l in loop) == 144          # two chunks of 72 slots
-    assert not any("v_accvgpr" in l for l in loop)
-    assert not any("scratch_" in l or "buffer_store" in l for l in loop)
+    begins = [i for i, l in enumerate(lines) if "; chunk loop begin" in l]
+    ends = [i for i, l in enumerate(lines) if "; chunk loop end" in l]
+    assert len(begins) == 2 and len(ends) == 2
+    for lo, hi in zip(begins, ends):
+        loop = lines[lo:hi]
+        assert 144 <= sum("v_mfma_f32_32x32x16_bf16" in l for l in loop) <= 160    # two chunks of 72 slots (+ what drifts in from the drain)
+        assert not any("v_accvgpr" in l for l in loop)
+        assert not any("scratch_" in l or "buffer_store" in l for l in loop)
