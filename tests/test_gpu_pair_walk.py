@@ -1,7 +1,8 @@
-"""Block size 128, bf16, d = 128: the attention kernel that walks pairs of adjacent query blocks, against the oracle on
-hand-made CSR lists that reach its corner cases (ownership patterns of the merged list, the sequence's last key block
-in its three shapes, an odd number of query blocks, empty rows, lists longer than one register window), and the
-single-row kernel it replaced kept under test through DR_ATTN_PAIRS=0.  Every row is compared."""
+"""Block sizes 128 and 64, bf16, d = 128: the attention kernel in which 256 queries (two or four adjacent query blocks)
+walk the merged list of their rows, against the oracle on hand-made CSR lists that reach its corner cases (ownership
+patterns of the merged list, the sequence's last key block in its shapes, a last group that is not full, empty rows,
+lists longer than one register window), and the kernels it replaced kept under test through DR_ATTN_PAIRS=0.  Every
+row is compared."""
 import dataclasses
 
 import numpy as np
@@ -18,9 +19,9 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2
 
 
-def _case(frames, hg, wg, H=2, seed_index=41):
-    """bf16, d = 128, block 128; N = frames * hg * wg."""
-    return dataclasses.replace(tiny_case("ragged128"), Nf=frames, Hg=hg, Wg=wg, H=H, index=seed_index)
+def _case(frames, hg, wg, H=2, seed_index=41, bs=128):
+    """bf16, d = 128; N = frames * hg * wg."""
+    return dataclasses.replace(tiny_case("ragged128"), Nf=frames, Hg=hg, Wg=wg, H=H, index=seed_index, Bs=bs)
 
 
 def _csr(rows, Sb):
@@ -68,15 +69,16 @@ def _rows(Sb, rng, density, force_last=None):
 
 
 @pytest.mark.parametrize("pairs", ["1", "0"])
+@pytest.mark.parametrize("bs", [128, 64])
 @pytest.mark.parametrize("frames,hg,wg,what", [
     (7, 9, 21, "last key block of 43 keys: a partial first chunk only"),        # N = 1323 = 10 * 128 + 43
-    (8, 10, 17, "last key block of 80 keys: one full chunk and a partial one"),  # N = 1360 = 10 * 128 + 80
+    (8, 10, 17, "last key block of 80 (16) keys: one full chunk and a partial one"),  # N = 1360 = 10 * 128 + 80
     (10, 8, 16, "last key block full"),                                           # N = 1280
     (3, 8, 24, "last key block of exactly 64 keys"),                              # N = 576 = 4 * 128 + 64
 ])
-def test_random_lists_against_the_oracle(frames, hg, wg, what, pairs, monkeypatch):
+def test_random_lists_against_the_oracle(frames, hg, wg, what, bs, pairs, monkeypatch):
     monkeypatch.setenv("DR_ATTN_PAIRS", pairs)
-    run = GpuRun(_case(frames, hg, wg))
+    run = GpuRun(_case(frames, hg, wg, bs=bs))
     Sb = run.wl.Sb
     rng = np.random.default_rng(frames * 100 + hg)
     rows = _rows(Sb, rng, 0.45)
@@ -84,6 +86,25 @@ def test_random_lists_against_the_oracle(frames, hg, wg, what, pairs, monkeypatc
     if Sb > 3:
         rows[2], rows[3] = [], []                           # a pair with nothing to do
     rows[1] = list(range(Sb))                               # a full row beside an empty one
+    rp, ci = _csr(rows, Sb)
+    _check(run, rp, ci)
+
+
+def test_ownership_patterns_of_four_rows_at_block_size_64(monkeypatch):
+    """Four query blocks per workgroup: every wave owns its own subset of the merged list (disjoint rows, one row that
+    lists everything beside three that list nothing, identical rows, the partial last key block listed by one wave
+    only), and the last group holds a single query block."""
+    monkeypatch.setenv("DR_ATTN_PAIRS", "1")
+    run = GpuRun(_case(8, 10, 17, bs=64))
+    Sb = run.wl.Sb                                           # 22: N = 1360 = 21 * 64 + 16; groups of four: 5 full + 2 blocks
+    assert Sb == 22
+    rows = [[] for _ in range(Sb)]
+    rows[0], rows[1], rows[2], rows[3] = [0, 4, 8, 12], [1, 5, 9, 21], [2, 6, 10], [3, 7, 11]      # disjoint
+    rows[4] = list(range(Sb))                                                                      # rows 5..7 empty
+    rows[8], rows[9], rows[10], rows[11] = [3, 20, 21], [3, 20, 21], [3, 20, 21], [3, 20, 21]      # identical
+    rows[12], rows[13], rows[14], rows[15] = [21], [0], [], [0, 21]                                # the partial block, owners vary
+    rows[16], rows[17], rows[18], rows[19] = [5, 6, 7, 8], [6, 7], [7], [4, 5, 6, 7, 8, 9]        # nested
+    rows[20], rows[21] = [0, 1, 21], [20]                                                          # the last group: two blocks
     rp, ci = _csr(rows, Sb)
     _check(run, rp, ci)
 
