@@ -81,7 +81,8 @@ def test_hand_scheduled_attention_kernel_compiles_without_spills_or_accumulator_
         r = subprocess.run([b.HIPCC, *[f for f in b.FLAGS if f != "-fPIC"], "-Rpass-analysis=kernel-resource-usage", "-S",
                             "--cuda-device-only", src, "-o", asm], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr[-2000:]
-        reports = [blk for blk in r.stderr.split("Function Name:")[1:] if "k_attn_mfma_pair" in blk or "k_attn_mfma_quad" in blk]
+        reports = [blk for blk in r.stderr.split("Function Name:")[1:]
+                   if "k_attn_mfma_pairE" in blk.splitlines()[0] or "k_attn_mfma_quadE" in blk.splitlines()[0]]
         assert len(reports) == 2                      # block size 128 and block size 64
         for report in reports:
             field = lambda name: int(re.search(name + r": (\d+)", report).group(1))
