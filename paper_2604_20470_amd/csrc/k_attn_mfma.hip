@@ -381,17 +381,31 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     attn_item<false>(a, item, smem);
 }
 
-// Second pass: the flagged items only.  Usually none is, so the grid is small and every workgroup steps through its
-// share of the flag words (a workgroup per item would spend 28 us at 23 640 items on starting workgroups that leave
-// at once).
+// Second pass: the flagged items only.  Usually none is, so the grid is small and every workgroup looks at a
+// contiguous share of the flag words, one item per thread and step (a workgroup per item would spend 28 us at 23 640
+// items on starting workgroups that leave at once; one item per workgroup and step, 27 us on dependent loads).
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_attn_mfma_second_pass(AttnArgs a) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    __shared__ unsigned char s_flagged[kThreads];
     const int total_items = a.Sb * a.td.H * a.td.B;
-    for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
-        const int4 f = *reinterpret_cast<const int4*>(a.flags + (int64_t)item * 4);
-        if (__builtin_amdgcn_readfirstlane(f.x | f.y | f.z | f.w) == 0) continue;
-        attn_item<true>(a, item, smem);
-        __syncthreads();          // the next item's tile loads overwrite LDS that slower waves may still be reading
+    const int per = (total_items + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int begin = min((int)blockIdx.x * per, total_items), end = min(begin + per, total_items);
+    for (int base = begin; base < end; base += kThreads) {
+        const int mine = base + (int)threadIdx.x;
+        int flagged = 0;
+        if (mine < end) {
+            const int4 f = *reinterpret_cast<const int4*>(a.flags + (int64_t)mine * 4);
+            flagged = (f.x | f.y | f.z | f.w) != 0;
+        }
+        if (!__syncthreads_or(flagged)) continue;
+        s_flagged[threadIdx.x] = (unsigned char)flagged;
+        __syncthreads();
+        for (int j = 0; j < kThreads && base + j < end; ++j) {
+            if (!s_flagged[j]) continue;          // the same for every thread
+            attn_item<true>(a, base + j, smem);
+            __syncthreads();          // the next item's tile loads overwrite LDS that slower waves may still be reading
+        }
+        __syncthreads();
     }
 }
 
