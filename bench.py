@@ -255,6 +255,7 @@ def main():
         "stages_ms_min": {"block_scores": round(st_min[0], 4), "build_mask": round(st_min[1], 4),
                           "sparse_attn_fwd": round(st_min[2], 4)},
         "effective_tflops": round(eff_tflops, 1),
+        "effective_tflops_whole_call": round(flop / (ms_per_step * 1e-3) / 1e12, 1),      # scores + mask + attention
         "dense_equivalent_tflops": round(dense_flop / (ms_attn * 1e-3) / 1e12, 1),
         "pct_bf16_mfma_peak": round(100.0 * eff_tflops / PEAK_BF16_TFLOPS, 2),
         "paper_context": "paper reports 1.7x-2.5x end-to-end speedup at >80% sparsity on NVIDIA H100 (not comparable)",
