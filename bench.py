@@ -313,6 +313,25 @@ def main():
                            "16x16x32": {"constant_operands": mfma_only(16, False), "random_operands": mfma_only(16, True)}}
     result["roofline"]["frac_of_measured_mfma_only_random"] = round(
         eff_tflops / result["mfma_only"]["32x32x16"]["random_operands"]["tflops"], 4)
+    # The same matrix instruction, one wave per SIMD, with one exponential and two fp32 instructions per slot: what a
+    # loop with the attention loop's kind of vector work beside every matrix instruction sustains with no memory
+    # traffic at all (matrix flop only are counted).
+    def mfma_mix():
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        dr.dr_mfma_mix_probe(ctx, 256, 2000, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        flop = 0.0
+        dr.dr_mfma_mix_probe(ctx, 256, 80000, sink)                      # ~15 ms per launch; the chip is at its working clock when timing starts
+        e0.record()
+        for _ in range(4):
+            flop += dr.dr_mfma_mix_probe(ctx, 256, 80000, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        return {"tflops": round(flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1),
+                "per_slot": "1 v_mfma_f32_32x32x16_bf16 + 1 v_exp_f32 + 2 v_fma_f32, random operands, one wave per SIMD"}
+    result["mfma_with_vector_mix"] = mfma_mix()
+    result["roofline"]["frac_of_measured_mfma_with_vector_mix"] = round(eff_tflops / result["mfma_with_vector_mix"]["tflops"], 4)
     # The scoring and mask stages are HBM/latency bound; with fused-head scoring (2 of 40 heads) they move only a few
     # MB, so their bandwidth is shown on the per-head variant (head_fuse = 0: every head scored, one mask per head).
     def timed(fn, iters=20):

@@ -35,6 +35,15 @@ dr_status dr_clock_probe(dr_ctx* ctx, uint64_t window_us, uint64_t* out, void* s
 dr_status dr_mfma_probe(dr_ctx* ctx, int32_t shape, int32_t workgroups, int32_t iters, int32_t random_operands,
                         float* sink, double* flop, void* stream);
 
+/* Measurement aid (not a step of the method): the matrix instruction in the company it has inside the attention
+ * loop.  Enqueues `workgroups` workgroups of 4 wavefronts, one wavefront per SIMD as in the attention kernels;
+ * every wavefront runs iters * 8 slots of one v_mfma_f32_32x32x16_bf16 on pseudo-random bf16 register operands,
+ * one v_exp_f32 and two v_fma_f32 (the attention loop has, per matrix instruction, 0.9 exponentials, 0.45 packs
+ * to bf16, 0.65 LDS fragment reads and about one scalar instruction).  The rate it reaches is what a loop of that
+ * instruction mix sustains on this device with no memory traffic at all.  `sink`, *flop (matrix flop only), timing
+ * and errors as for dr_mfma_probe; workgroups * iters may not exceed 2^26. */
+dr_status dr_mfma_mix_probe(dr_ctx* ctx, int32_t workgroups, int32_t iters, float* sink, double* flop, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -79,7 +79,8 @@ def load_library():
     lib.dr_proxy_loss.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, i32, f64, f64, vp, vp]
     lib.dr_clock_probe.argtypes = [vp, C.c_uint64, vp, vp]
     lib.dr_mfma_probe.argtypes = [vp, i32, i32, i32, i32, vp, C.POINTER(f64), vp]
-    for name in ("dr_token_scores", "dr_build_mask_tokens", "dr_proxy_loss", "dr_static_ratio_for_sparsity", "dr_clock_probe", "dr_mfma_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
+    lib.dr_mfma_mix_probe.argtypes = [vp, i32, i32, vp, C.POINTER(f64), vp]
+    for name in ("dr_token_scores", "dr_build_mask_tokens", "dr_proxy_loss", "dr_static_ratio_for_sparsity", "dr_clock_probe", "dr_mfma_probe", "dr_mfma_mix_probe", "dr_create", "dr_class_map", "dr_mask_capacity", "dr_block_scores", "dr_build_mask",
                  "dr_sparse_attn_fwd", "dr_sparse_attn_fwd_static"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -216,4 +217,11 @@ def dr_mfma_probe(ctx: Context, shape: int, workgroups: int, iters: int, random_
     flop = C.c_double(0.0)
     ctx.check(ctx._lib.dr_mfma_probe(ctx._h, int(shape), int(workgroups), int(iters), 1 if random_operands else 0,
                                      _ptr(sink), C.byref(flop), _stream(stream)))
+    return flop.value
+
+
+def dr_mfma_mix_probe(ctx: Context, workgroups: int, iters: int, sink, stream=None) -> float:
+    """Enqueue the loop of one 32x32x16 matrix instruction + one exponential + two fp32 instructions per slot."""
+    flop = C.c_double(0.0)
+    ctx.check(ctx._lib.dr_mfma_mix_probe(ctx._h, int(workgroups), int(iters), _ptr(sink), C.byref(flop), _stream(stream)))
     return flop.value

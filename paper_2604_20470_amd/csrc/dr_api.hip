@@ -655,4 +655,18 @@ dr_status dr_mfma_probe(dr_ctx* ctx, int32_t shape, int32_t workgroups, int32_t 
     return DR_OK;
 }
 
+dr_status dr_mfma_mix_probe(dr_ctx* ctx, int32_t workgroups, int32_t iters, float* sink, double* flop, void* stream) {
+    if (!ctx) return DR_ERR_INVALID_ARG;
+    if (!sink) return fail(ctx, DR_ERR_INVALID_ARG, "NULL sink pointer");
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0 || iters > (1 << 24))
+        return fail(ctx, DR_ERR_INVALID_ARG, "workgroups must be 1 .. 2^20 and iters 1 .. 2^24");
+    // the kernel cannot be pre-empted: keep a launch to tens of milliseconds on a full device
+    if ((int64_t)workgroups * iters > (1ll << 26))
+        return fail(ctx, DR_ERR_INVALID_ARG, "workgroups * iters = %lld exceeds 2^26", (long long)workgroups * iters);
+    DeviceGuard g(ctx->device);
+    DR_HIP(ctx, launch_mfma_mix_probe(workgroups, iters, sink, (hipStream_t)stream));
+    if (flop) *flop = (double)workgroups * 4.0 * (double)iters * 8.0 * 32768.0;
+    return DR_OK;
+}
+
 }  // extern "C"

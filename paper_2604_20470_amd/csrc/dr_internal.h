@@ -126,5 +126,6 @@ hipError_t launch_proxy_loss(const float* A_dense, const float* A_sparse, int BH
 hipError_t launch_clock_probe(unsigned long long window_ticks, unsigned long long* out, hipStream_t s);
 // MFMA-only loop: workgroups x 4 waves x iters x 8 matrix instructions; shape 32 (32x32x16) or 16 (16x16x32).
 hipError_t launch_mfma_probe(int shape, int workgroups, int iters, int random_operands, float* sink, hipStream_t s);
+hipError_t launch_mfma_mix_probe(int workgroups, int iters, float* sink, hipStream_t s);
 
 }  // namespace dr

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_measurement_aids_are_not_in_the_product_header():
     product, probes = _declared(), _declared("dynamicrad_probe.h")
-    assert probes == ["dr_clock_probe", "dr_mfma_probe"]
+    assert probes == ["dr_clock_probe", "dr_mfma_mix_probe", "dr_mfma_probe"]
     assert not set(product) & set(probes)
     assert "dr_proxy_loss" in product
 

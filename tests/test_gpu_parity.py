@@ -575,3 +575,8 @@ def test_mfma_probe_runs_and_checks_its_arguments():
     for shape, wg, it in ((32, 0, 16), (32, 8, 0), (32, 8, 12), (8, 8, 16), (32, 1 << 20, 1 << 10), (16, 1 << 12, 1 << 24)):
         with pytest.raises(dr.DRError):
             dr.dr_mfma_probe(ctx, shape, wg, it, False, sink)
+    assert dr.dr_mfma_mix_probe(ctx, 8, 16, sink) == 8 * 4 * 16 * 8 * 32768.0
+    torch.cuda.synchronize()
+    for wg, it in ((0, 16), (8, 0), (1 << 20, 1 << 10)):
+        with pytest.raises(dr.DRError):
+            dr.dr_mfma_mix_probe(ctx, wg, it, sink)
