@@ -276,12 +276,16 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
 
 // Static top-k / seeded sample for rows of at most 1024 key blocks: ONE wave per row, four rows per workgroup, no LDS and
 // no barrier.  Lane l holds the keys of key blocks l, l + 64, ... in registers, complemented and split into two words
-// (kSlots of them; a key that does not exist or is out of the running is the word pair 0).  The k-th smallest key is
-// found bit by bit from the top: per register one AND, one compare into a lane mask and a population count; the
-// key-index bits above log2(Sb) are zero in every key and skipped, and once a single candidate is left it is the
-// answer.  A ballot of "selected" over the wave IS the pair of keep words of those 64 key blocks.  Same keys, same
-// counts, same comparisons as k_select: the keep bitmaps are identical.  With one workgroup per row, k_select holds
-// 8 rows per CU in flight, each waiting on its barriers; this holds up to 32.
+// (kSlots of them; a key that does not exist is the word pair 0).  The rules need the SET of the k smallest keys, not
+// their order, and the keys are distinct, so any threshold that exactly k complemented keys reach describes it.  The
+// threshold is built bit by bit from the top: with the bits kept so far and the next one set, count the keys that
+// reach it -- per register one unsigned compare into a lane mask and a population count, nothing is rewritten; keep
+// the bit when at least k do, and stop as soon as exactly k do (at the highest bit in which the k-th and the
+// (k+1)-th key differ: a dozen to twenty steps on real scores).  Only when keys with equal high words straddle rank
+// k (equal scores) does the search go on in the low words of that group; the key-index bits above log2(Sb) are equal
+// in every key and take no vote.  A ballot of "selected" over the wave IS the pair of keep words of those 64 key
+// blocks.  Same keys, same counts as k_select: the keep bitmaps are identical.  With one workgroup per row, k_select
+// holds 8 rows per CU in flight, each waiting on its barriers; this holds up to 32.
 // grid: ceil(B * masks * Sb / 4).
 constexpr int kWaveSelectMaxSlots = 16;
 constexpr int64_t kWaveSelectMinRows = 2048;
@@ -292,45 +296,40 @@ struct WaveKeys {
     uint32_t nhi[kSlots], nlo[kSlots];            // ~key, high and low word; (0, 0) = no key here
 };
 
+// selected <=> the complemented key, as a 64-bit number, is at least (hi, lo); never (0, 0)
+struct WaveThreshold {
+    uint32_t hi, lo;
+};
+
 template <int kSlots>
-__device__ __forceinline__ uint64_t kth_smallest_wave(WaveKeys<kSlots> w, int n, int k, int index_bits) {
-    uint64_t prefix = 0ull;
-    int rank = k, n_alive = n;
-    // one bit of the answer: the candidates with a 0 there are the smaller ones
-    auto step = [&](const uint32_t (&word)[kSlots], uint32_t mask) -> bool {
-        int cnt0 = 0;
+__device__ __forceinline__ WaveThreshold kth_smallest_wave(const WaveKeys<kSlots>& w, int k, int index_bits) {
+    uint32_t t_hi = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t t = t_hi | (1u << bit);
+        int cnt = 0;
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) cnt0 += __popcll(__ballot((word[i] & mask) != 0u));
-        const bool low = rank <= cnt0;            // wave-uniform
-        if (cnt0 != 0 && cnt0 != n_alive) {       // otherwise every candidate has the same bit here and all stay
-#pragma unroll
-            for (int i = 0; i < kSlots; ++i) {
-                const bool zero_here = (word[i] & mask) != 0u;
-                const bool out = low ? !zero_here : zero_here;
-                w.nhi[i] = out ? 0u : w.nhi[i];
-                w.nlo[i] = out ? 0u : w.nlo[i];
-            }
-        }
-        if (!low) rank -= cnt0;
-        n_alive = low ? cnt0 : n_alive - cnt0;
-        return !low;
-    };
-    for (int bit = 31; bit >= 0 && n_alive > 1; --bit)
-        if (step(w.nhi, 1u << bit)) prefix |= 1ull << (32 + bit);
-    if (n_alive > 1 && step(w.nlo, 1u << 31)) prefix |= 1ull << 31;
-    for (int bit = index_bits - 1; bit >= 0 && n_alive > 1; --bit)
-        if (step(w.nlo, 1u << bit)) prefix |= 1ull << bit;
-    if (n_alive == 1) {
-        // every live key has a 0 at bit 30, so its complemented low word is not 0: exactly one lane finds its own
-        uint32_t hi = 0u, lo = 0u;
-#pragma unroll
-        for (int i = 0; i < kSlots; ++i) { hi |= w.nhi[i]; lo |= w.nlo[i]; }
-        const int src = __ffsll((unsigned long long)__ballot(lo != 0u)) - 1;
-        hi = __shfl(hi, src);
-        lo = __shfl(lo, src);
-        return ~(((uint64_t)hi << 32) | (uint64_t)lo);
+        for (int i = 0; i < kSlots; ++i) cnt += __popcll(__ballot(w.nhi[i] >= t));
+        if (cnt == k) return WaveThreshold{t, 0u};    // wave-uniform
+        if (cnt > k) t_hi = t;
     }
-    return prefix;
+    // t_hi is the high word of the k-th largest complemented key, and more keys than rank k asks for share it
+    int above = 0;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) above += __popcll(__ballot(w.nhi[i] > t_hi));
+    const int k_low = k - above;
+    uint32_t t_lo = 0x7fffffffu & ~((1u << index_bits) - 1u);   // ones in every key: the index bits no key block has
+    auto vote = [&](uint32_t bit_mask) -> bool {
+        const uint32_t t = t_lo | bit_mask;
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) cnt += __popcll(__ballot(w.nhi[i] == t_hi && w.nlo[i] >= t));
+        if (cnt >= k_low) t_lo = t;
+        return cnt == k_low;
+    };
+    if (vote(1u << 31)) return WaveThreshold{t_hi, t_lo};
+    for (int bit = index_bits - 1; bit >= 0; --bit)
+        if (vote(1u << bit)) break;
+    return WaveThreshold{t_hi, t_lo};
 }
 
 template <int kSlots>
@@ -348,38 +347,52 @@ __global__ __launch_bounds__(kThreads) void k_select_wave(const uint8_t* __restr
     int index_bits = 0;
     while ((1 << index_bits) < Sb) ++index_bits;
 
+    // every load of the row is issued before the first is used: the classes and (for the score rules) the scores of
+    // all kSlots * 64 positions, positions past the row's end reading its last entry; no load waits on a branch
+    int cls[kSlots];
+    float sc[kSlots];
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) cls[i] = crow[min(i * 64 + lane, Sb - 1)];
+    if (a.mode != 3) {
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) sc[i] = srow[min(i * 64 + lane, Sb - 1)];
+    } else {
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) sc[i] = 0.f;
+    }
     WaveKeys<kSlots> w;
     uint64_t forced = 0ull;                       // bit i: key block i * 64 + lane is kept whatever its score
     int n = 0, n_near_cnt = 0;
 #pragma unroll
     for (int i = 0; i < kSlots; ++i) {
         const int kb = i * 64 + lane;
-        const int c = (kb < Sb) ? crow[kb] : 0;
+        const int c = (kb < Sb) ? cls[i] : 0;
         const bool selectable = c == 1 || c == 2;
         const bool far_bit = a.two_ratio && c == 2;
-        uint64_t key = ~0ull;
-        if (selectable) key = (a.mode == 3) ? make_sample_key(a.seed, qb, kb, far_bit) : make_key(srow[kb], kb, far_bit);
-        w.nhi[i] = ~(uint32_t)(key >> 32);
-        w.nlo[i] = ~(uint32_t)key;
+        const uint64_t key = (a.mode == 3) ? make_sample_key(a.seed, qb, kb, far_bit) : make_key(sc[i], kb, far_bit);
+        w.nhi[i] = selectable ? ~(uint32_t)(key >> 32) : 0u;
+        w.nlo[i] = selectable ? ~(uint32_t)key : 0u;
         forced |= (uint64_t)(c == 3 ? 1 : 0) << i;
         n += __popcll(__ballot(selectable));
         n_near_cnt += __popcll(__ballot(selectable && c == 1));
     }
-    uint64_t t_near = 0ull, t_far = 0ull;
+    WaveThreshold t_near{0u, 0u}, t_far{0u, 0u};
     int k_near = 0, k_far = 0;
     if (n > 0) {
         const int n_near = a.two_ratio ? n_near_cnt : n;
         k_near = keep_count(n_near, a.ratio);
         k_far = a.two_ratio ? keep_count(n - n_near, a.ratio_far) : 0;
-        if (k_near > 0) t_near = kth_smallest_wave<kSlots>(w, n, k_near, index_bits);
-        if (k_far > 0) t_far = kth_smallest_wave<kSlots>(w, n, n_near + k_far, index_bits);
+        if (k_near > 0) t_near = kth_smallest_wave<kSlots>(w, k_near, index_bits);
+        if (k_far > 0) t_far = kth_smallest_wave<kSlots>(w, n_near + k_far, index_bits);
     }
     int kept = 0;
 #pragma unroll
     for (int i = 0; i < kSlots; ++i) {
-        const uint64_t key = ~(((uint64_t)w.nhi[i] << 32) | (uint64_t)w.nlo[i]);
-        const bool is_key = w.nlo[i] != 0u, far_key = (key >> 63) != 0;
-        const bool sel = is_key && (far_key ? (k_far > 0 && key <= t_far) : (k_near > 0 && key <= t_near));
+        // a far key has bit 63 set, so its complement has it clear; a word pair of 0 reaches no threshold
+        const bool far_key = (w.nhi[i] >> 31) == 0u;
+        const WaveThreshold t = far_key ? t_far : t_near;
+        const bool ranked = far_key ? k_far > 0 : k_near > 0;
+        const bool sel = ranked && (w.nhi[i] > t.hi || (w.nhi[i] == t.hi && w.nlo[i] >= t.lo));
         const uint64_t m = __ballot(sel || ((forced >> i) & 1ull));
         kept += __popcll(m);
         if (lane < 2 && 2 * i + lane < words) keepbits[row * words + 2 * i + lane] = (uint32_t)(m >> (32 * lane));
@@ -629,8 +642,11 @@ hipError_t launch_select_zscore(const uint8_t* class_map, const float* scores, i
     return hipGetLastError();
 }
 
-// The same for rows of at most 2048 key blocks (64 bitmap words): one wave per row, a word per lane, no LDS and no
-// barrier; four rows per workgroup.  grid: ceil(B * masks * Sb / 4).
+// The same for rows of at most 2048 key blocks (64 bitmap words): one wave per row, no LDS and no barrier; four rows per
+// workgroup.  A lane loads one bitmap word; the wave then walks the row 64 key blocks at a time: the two words of that
+// stretch are read back as a wave-uniform lane mask, a lane whose bit is set stores its key block at the running
+// offset plus the number of set bits below it (v_mbcnt), so that each store instruction writes one contiguous run.
+// grid: ceil(B * masks * Sb / 4).
 __global__ __launch_bounds__(kThreads) void k_emit_wave(const uint32_t* __restrict__ keepbits, int64_t rows_total, int Sb,
                                                         int shared, const int32_t* __restrict__ rowptr,
                                                         int32_t* __restrict__ colidx, int64_t capacity) {
@@ -642,20 +658,15 @@ __global__ __launch_bounds__(kThreads) void k_emit_wave(const uint32_t* __restri
     const int64_t row = shared ? qb : r;
     const int words = (Sb + 31) / 32;
     const uint32_t wv = (lane < words) ? keepbits[row * words + lane] : 0u;
-    const int c = __popc(wv);
-    int incl = c;
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(incl, o);
-        if (lane >= o) incl += t;
-    }
-    long long pos = (long long)rowptr[mask_id * (Sb + 1) + qb] + incl - c;   // negative only past 32-bit offsets
+    long long pos = (long long)rowptr[mask_id * (Sb + 1) + qb];            // negative only past 32-bit offsets
     int32_t* out = colidx + mask_id * capacity;
-    uint32_t bits = wv;
-    while (bits) {
-        const int bit = __ffs(bits) - 1;
-        bits &= bits - 1;
-        if (pos >= 0 && pos < capacity) out[pos] = lane * 32 + bit;
-        ++pos;
+    const int stretches = (Sb + 63) / 64;
+    for (int i = 0; i < stretches; ++i) {                                  // wave-uniform
+        const uint32_t lo = __builtin_amdgcn_readlane(wv, 2 * i), hi = __builtin_amdgcn_readlane(wv, 2 * i + 1);
+        const uint32_t mine = (lane < 32) ? (lo >> lane) : (hi >> (lane - 32));
+        const long long p = pos + (int)__builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+        if ((mine & 1u) && p >= 0 && p < capacity) out[p] = i * 64 + lane;
+        pos += __popc(lo) + __popc(hi);
     }
 }
 
