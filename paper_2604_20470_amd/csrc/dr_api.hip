@@ -52,6 +52,8 @@ struct dr_ctx {
     size_t links_bytes = 0;
     // cached candidate geometry
     uint8_t* class_map = nullptr;
+    uint64_t* class_bits = nullptr;      // the classes as lane masks (block rows of at most kWaveSelectMaxBlocks)
+    size_t class_bits_bytes = 0;
     int32_t* row_sel = nullptr;
     unsigned long long* totals = nullptr;     // device [2]
     size_t class_bytes = 0, rowsel_bytes = 0;
@@ -210,12 +212,15 @@ dr_status ensure_geometry(dr_ctx* ctx, const dr_shape* s, double lambda, const d
     dr_status st;
     if ((st = grow(ctx, (void**)&ctx->class_map, &ctx->class_bytes, (size_t)Sb * Sb)) != DR_OK) return st;
     if ((st = grow(ctx, (void**)&ctx->row_sel, &ctx->rowsel_bytes, (size_t)Sb * 4)) != DR_OK) return st;
+    const bool lane_masks = Sb <= kWaveSelectMaxBlocks;
+    if (lane_masks && (st = grow(ctx, (void**)&ctx->class_bits, &ctx->class_bits_bytes,
+                                 (size_t)Sb * wave_select_slots(Sb) * 3 * sizeof(uint64_t))) != DR_OK) return st;
     if (!ctx->totals) DR_HIP(ctx, hipMalloc((void**)&ctx->totals, 2 * sizeof(unsigned long long)));
     const Geometry g = make_geometry(s, p);
     FrameTab tab;
     fill_frame_table(s->Nf, Nt, s->Bs, p->gamma, lambda, &tab);
     DR_HIP(ctx, hipMemsetAsync(ctx->totals, 0, 2 * sizeof(unsigned long long), stream));
-    DR_HIP(ctx, launch_class_map(g, tab, ctx->class_map, ctx->row_sel, ctx->totals, stream));
+    DR_HIP(ctx, launch_class_map(g, tab, ctx->class_map, lane_masks ? ctx->class_bits : nullptr, ctx->row_sel, ctx->totals, stream));
     unsigned long long host_tot[2] = {0, 0};
     DR_HIP(ctx, hipMemcpyAsync(host_tot, ctx->totals, sizeof host_tot, hipMemcpyDeviceToHost, stream));
     DR_HIP(ctx, hipStreamSynchronize(stream));
@@ -259,7 +264,7 @@ void dr_destroy(dr_ctx* ctx) {
     if (!ctx) return;
     {
         DeviceGuard g(ctx->device);
-        void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->row_sel, ctx->totals, ctx->gcol,
+        void* ptrs[] = {ctx->pooled, ctx->keepbits, ctx->counts, ctx->class_map, ctx->class_bits, ctx->row_sel, ctx->totals, ctx->gcol,
                         ctx->gcount, ctx->attn_flags, ctx->uni_keep, ctx->uni_counts, ctx->links, ctx->proxy_partial};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
@@ -424,7 +429,7 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
         uk.ratio = ratio_or_tau; uk.ratio_far = p->ratio_far; uk.seed = p->seed;
         if (!ctx->uni_valid || std::memcmp(&uk, &ctx->uni_key, sizeof uk) != 0) {
             ctx->uni_valid = false;
-            DR_HIP(ctx, launch_select(ctx->class_map, nullptr, 1, 1, Sb, a, ctx->uni_keep, ctx->uni_counts, s));
+            DR_HIP(ctx, launch_select(ctx->class_map, Sb <= kWaveSelectMaxBlocks ? ctx->class_bits : nullptr, nullptr, 1, 1, Sb, a, ctx->uni_keep, ctx->uni_counts, s));
             std::memcpy(&ctx->uni_key, &uk, sizeof uk);
             ctx->uni_valid = true;
         }
@@ -440,7 +445,7 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
     if (mode == DR_MODE_ZSCORE_THRESHOLD)
         DR_HIP(ctx, launch_select_zscore(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
     else
-        DR_HIP(ctx, launch_select(ctx->class_map, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
+        DR_HIP(ctx, launch_select(ctx->class_map, Sb <= kWaveSelectMaxBlocks ? ctx->class_bits : nullptr, scores, shape->B, masks, Sb, a, ctx->keepbits, ctx->counts, s));
     DR_HIP(ctx, launch_emit(ctx->keepbits, ctx->counts, shape->B, masks, Sb, false, rowptr, colidx, colidx_capacity, nnz, s));
     return DR_OK;
 }

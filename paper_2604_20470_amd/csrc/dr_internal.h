@@ -40,8 +40,12 @@ hipError_t launch_scores(const float* pooled, int B, int Hs, int masks, int head
 
 // ---- stage (b) -------------------------------------------------------------------------
 // class_map[qb][kb]; row_sel[qb] = NEAR+FAR count of the row; totals[0] += candidates, totals[1] = max row_sel.
-hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* class_map, int32_t* row_sel,
-                            unsigned long long* totals, hipStream_t s);
+// class_bits (may be NULL; else Sb * wave_select_slots(Sb) * 3 words, for Sb <= kWaveSelectMaxBlocks): the same classes
+// as one lane mask per 64 key blocks -- selectable, FAR, forced -- which the one-wave-per-row selection reads.
+constexpr int kWaveSelectMaxBlocks = 1024;
+int wave_select_slots(int Sb);
+hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* class_map, uint64_t* class_bits,
+                            int32_t* row_sel, unsigned long long* totals, hipStream_t s);
 struct SelectArgs {
     int32_t mode;            // dr_mode: 0 static top-k, 1 cumulative mass, 2 z-score thresholds, 3 seeded uniform sample
     int32_t two_ratio;       // static / uniform: rank NEAR and FAR separately
@@ -53,8 +57,8 @@ struct SelectArgs {
     uint64_t near_mask[kMaxFrames / 64];   // z-score mode: bit t set when the decay length at frame distance t is >= Bs
 };
 // keepbits[(b*masks+m)*Sb + qb][words], counts[(b*masks+m)*Sb + qb]
-hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
-                         const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
+hipError_t launch_select(const uint8_t* class_map, const uint64_t* class_bits, const float* scores, int B, int masks,
+                         int Sb, const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s);
 // z-score mode (paper Eqs. 10-11 at block level); same outputs as launch_select.  Its kernel holds one row's scores
 // in LDS as a [key blocks per frame + 1][Nf] tile beside the keep bitmap: geometries beyond the limit are refused.
 constexpr size_t kSelectZscoreMaxLds = 144 * 1024;

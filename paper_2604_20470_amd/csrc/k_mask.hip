@@ -274,26 +274,28 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
     store_row(keep, words, row, keepbits, counts, &s_cnt);
 }
 
-// Static top-k / seeded sample for rows of at most 1024 key blocks: ONE wave per row, four rows per workgroup, no LDS and
-// no barrier.  Lane l holds the keys of key blocks l, l + 64, ... in registers, complemented and split into two words
-// (kSlots of them; a key that does not exist is the word pair 0).  The rules need the SET of the k smallest keys, not
-// their order, and the keys are distinct, so any threshold that exactly k complemented keys reach describes it.  The
-// threshold is built bit by bit from the top: with the bits kept so far and the next one set, count the keys that
-// reach it -- per register one unsigned compare into a lane mask and a population count, nothing is rewritten; keep
-// the bit when at least k do, and stop as soon as exactly k do (at the highest bit in which the k-th and the
-// (k+1)-th key differ: a dozen to twenty steps on real scores).  Only when keys with equal high words straddle rank
-// k (equal scores) does the search go on in the low words of that group; the key-index bits above log2(Sb) are equal
-// in every key and take no vote.  A ballot of "selected" over the wave IS the pair of keep words of those 64 key
-// blocks.  Same keys, same counts as k_select: the keep bitmaps are identical.  With one workgroup per row, k_select
-// holds 8 rows per CU in flight, each waiting on its barriers; this holds up to 32.
+// Static top-k / seeded sample for rows of at most 1024 key blocks: ONE wave per row, four rows per workgroup, no
+// barrier.  Lane l holds the keys of key blocks l, l + 64, ... in registers, complemented (kSlots 64-bit values; 0
+// where there is no key).  The classes arrive as lane masks (k_class_bits), so counting the selectable and the FAR
+// keys, dropping the others and adding the forced ones are scalar operations on those masks.  The rules need the SET
+// of the k smallest keys, not their order, and the keys are distinct, so any threshold that exactly k complemented
+// keys reach describes it.  The threshold is built bit by bit from the top: with the bits kept so far and the next
+// one set, count the keys that reach it -- per register one unsigned compare into a lane mask and a population
+// count, nothing is rewritten; keep the bit when at least k do, and stop as soon as exactly k do (at the highest bit
+// in which the k-th and the (k+1)-th key differ: 15 to 20 steps on real scores).  Only when keys with equal high
+// words straddle rank k (equal scores) does the search go on in the low words of that group; the key-index bits
+// above log2(Sb) are equal in every key and take no vote.  For a small k the search runs on a short list of one
+// register instead (kth_smallest_wave_short_list).  A ballot of "selected" over the wave IS the pair of keep words
+// of those 64 key blocks.  Same keys, same counts as k_select: the keep bitmaps are identical.  With one workgroup
+// per row, k_select holds 8 rows per CU in flight, each waiting on its barriers; this holds up to 32.
 // grid: ceil(B * masks * Sb / 4).
-constexpr int kWaveSelectMaxSlots = 16;
+constexpr int kWaveSelectMaxSlots = kWaveSelectMaxBlocks / 64;
 constexpr int64_t kWaveSelectMinRows = 2048;
 static_assert(kWaveSelectMaxSlots <= 64, "one bit per slot in a 64-bit word");
 
 template <int kSlots>
 struct WaveKeys {
-    uint32_t nhi[kSlots], nlo[kSlots];            // ~key, high and low word; (0, 0) = no key here
+    uint64_t c[kSlots];                           // ~key; 0 = no key here
 };
 
 // selected <=> the complemented key, as a 64-bit number, is at least (hi, lo); never (0, 0)
@@ -308,21 +310,22 @@ __device__ __forceinline__ WaveThreshold kth_smallest_wave(const WaveKeys<kSlots
         const uint32_t t = t_hi | (1u << bit);
         int cnt = 0;
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) cnt += __popcll(__ballot(w.nhi[i] >= t));
+        for (int i = 0; i < kSlots; ++i) cnt += __popcll(__ballot((uint32_t)(w.c[i] >> 32) >= t));
         if (cnt == k) return WaveThreshold{t, 0u};    // wave-uniform
         if (cnt > k) t_hi = t;
     }
     // t_hi is the high word of the k-th largest complemented key, and more keys than rank k asks for share it
     int above = 0;
 #pragma unroll
-    for (int i = 0; i < kSlots; ++i) above += __popcll(__ballot(w.nhi[i] > t_hi));
+    for (int i = 0; i < kSlots; ++i) above += __popcll(__ballot((uint32_t)(w.c[i] >> 32) > t_hi));
     const int k_low = k - above;
     uint32_t t_lo = 0x7fffffffu & ~((1u << index_bits) - 1u);   // ones in every key: the index bits no key block has
     auto vote = [&](uint32_t bit_mask) -> bool {
         const uint32_t t = t_lo | bit_mask;
         int cnt = 0;
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) cnt += __popcll(__ballot(w.nhi[i] == t_hi && w.nlo[i] >= t));
+        for (int i = 0; i < kSlots; ++i)
+            cnt += __popcll(__ballot((uint32_t)(w.c[i] >> 32) == t_hi && (uint32_t)w.c[i] >= t));
         if (cnt >= k_low) t_lo = t;
         return cnt == k_low;
     };
@@ -332,70 +335,156 @@ __device__ __forceinline__ WaveThreshold kth_smallest_wave(const WaveKeys<kSlots
     return WaveThreshold{t_hi, t_lo};
 }
 
+// The same answer for a small k, by way of a short list.  The k-th largest of the 64 lanes' own maxima is a lower
+// bound of the k-th largest key, so the keys that reach it hold the k largest; when they are at most 64 (a few more
+// than k on real scores) they are packed one per lane through `list` (64 words of LDS that belong to this wave)
+// and the search runs on one register instead of kSlots.  Only the high words take part in the bound, so keys with
+// equal high words all make the list.  Returns false, with nothing decided, when the list would not fit or fewer
+// than k lanes hold a key.
+constexpr int kShortListMaxK = 40;
+
 template <int kSlots>
-__global__ __launch_bounds__(kThreads) void k_select_wave(const uint8_t* __restrict__ class_map,
+__device__ __forceinline__ bool kth_smallest_wave_short_list(const WaveKeys<kSlots>& w, int k, int index_bits,
+                                                             uint64_t* list, WaveThreshold* out) {
+    uint32_t lane_max = 0u;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) lane_max = max(lane_max, (uint32_t)(w.c[i] >> 32));
+    uint32_t bound = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t t = bound | (1u << bit);
+        const int cnt = __popcll(__ballot(lane_max >= t));
+        if (cnt >= k) bound = t;
+        if (cnt == k) break;
+    }
+    if (bound == 0u) return false;
+    uint64_t reach[kSlots];
+    int listed = 0;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) {
+        reach[i] = __ballot((uint32_t)(w.c[i] >> 32) >= bound);
+        listed += __popcll(reach[i]);
+    }
+    if (listed > 64) return false;
+    if (listed == k) {                            // the list is the answer
+        *out = WaveThreshold{bound, 0u};
+        return true;
+    }
+    int at = 0;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) {
+        const int mine = at + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(reach[i] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)reach[i], 0u));
+        if (__builtin_amdgcn_inverse_ballot_w64(reach[i])) list[mine] = w.c[i];
+        at += __popcll(reach[i]);
+    }
+    // the wave's LDS operations execute in order; the fence keeps the compiler from moving the read above the writes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    WaveKeys<1> shortlist;
+    shortlist.c[0] = (lane_id() < listed) ? list[lane_id()] : 0ull;
+    __builtin_amdgcn_wave_barrier();
+    // more keys than k are listed, so the threshold found lies above the bound and counts the same keys in the row
+    *out = kth_smallest_wave<1>(shortlist, k, index_bits);
+    return true;
+}
+
+// The class map as lane masks, for the one-wave-per-row selection: class_bits[qb][slot][3] holds, for the 64 key
+// blocks of a slot, one bit per key block: selectable (NEAR or FAR), FAR, forced.  A row has `slots` entries, the
+// register slots of the selection kernel that will read it; those past the row's end are 0.  Written once per
+// geometry.  grid: ceil(Sb / 4); one wave per row.
+__global__ __launch_bounds__(kThreads) void k_class_bits(const uint8_t* __restrict__ class_map, int Sb, int slots,
+                                                         uint64_t* __restrict__ class_bits) {
+    const int lane = lane_id(), qb = blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (qb >= Sb) return;
+    for (int i = 0; i < slots; ++i) {
+        const int kb = i * 64 + lane;
+        const int c = (kb < Sb) ? class_map[(int64_t)qb * Sb + kb] : 0;
+        const uint64_t sel = __ballot(c == 1 || c == 2), far = __ballot(c == 2), forced = __ballot(c == 3);
+        if (lane < 3) class_bits[((int64_t)qb * slots + i) * 3 + lane] = lane == 0 ? sel : lane == 1 ? far : forced;
+    }
+}
+
+// ascending unsigned == ascending float, -0 counted as +0
+__device__ __forceinline__ uint32_t score_image(float s) {
+    const uint32_t u = __float_as_uint(s + 0.0f);
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+}
+
+template <int kSlots>
+__global__ __launch_bounds__(kThreads) void k_select_wave(const uint64_t* __restrict__ class_bits,
                                                           const float* __restrict__ scores, int64_t rows_total, int Sb,
                                                           SelectArgs a, uint32_t* __restrict__ keepbits,
                                                           int32_t* __restrict__ counts) {
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
+    __shared__ uint64_t s_list[kWaves][64];                       // a wave's short list of candidate keys
+    const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row = (int64_t)blockIdx.x * kWaves + wave;      // the same in every lane, and known to be
     if (row >= rows_total) return;
     const int qb = (int)(row % Sb);
     const float* srow = scores + row * Sb;
-    const uint8_t* crow = class_map + (int64_t)qb * Sb;
     const int words = (Sb + 31) / 32;
+    const uint64_t* cb = class_bits + (int64_t)qb * (kSlots * 3);
     int index_bits = 0;
     while ((1 << index_bits) < Sb) ++index_bits;
 
-    // every load of the row is issued before the first is used: the classes and (for the score rules) the scores of
-    // all kSlots * 64 positions, positions past the row's end reading its last entry; no load waits on a branch
-    int cls[kSlots];
+    // every load of the row is issued before the first is used: the scores of all kSlots * 64 positions (those past
+    // the row's end read its last entry) and the lane masks of the classes
     float sc[kSlots];
-#pragma unroll
-    for (int i = 0; i < kSlots; ++i) cls[i] = crow[min(i * 64 + lane, Sb - 1)];
     if (a.mode != 3) {
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) sc[i] = srow[min(i * 64 + lane, Sb - 1)];
+        for (int i = 0; i < kSlots; ++i) sc[i] = srow[(uint32_t)min(i * 64 + lane, Sb - 1)];
     } else {
 #pragma unroll
         for (int i = 0; i < kSlots; ++i) sc[i] = 0.f;
     }
+    uint64_t m_sel[kSlots], m_far[kSlots], m_forced[kSlots];
+    const uint64_t ranked_apart = a.two_ratio ? ~0ull : 0ull;
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) {
+        m_sel[i] = cb[i * 3 + 0];
+        m_far[i] = cb[i * 3 + 1] & ranked_apart;
+        m_forced[i] = cb[i * 3 + 2];
+    }
+    // complemented key of key block kb: (not FAR) << 63 | image << 31 | ~kb (31 bits), the image being the order-preserving
+    // integer of the score (or the complement of the sample hash); 0 where the class selects nothing
     WaveKeys<kSlots> w;
-    uint64_t forced = 0ull;                       // bit i: key block i * 64 + lane is kept whatever its score
-    int n = 0, n_near_cnt = 0;
+    int n = 0, n_far = 0;
+    const uint32_t seed_row = (a.mode == 3) ? fmix32(a.seed ^ fmix32((uint32_t)qb)) : 0u;
 #pragma unroll
     for (int i = 0; i < kSlots; ++i) {
         const int kb = i * 64 + lane;
-        const int c = (kb < Sb) ? cls[i] : 0;
-        const bool selectable = c == 1 || c == 2;
-        const bool far_bit = a.two_ratio && c == 2;
-        const uint64_t key = (a.mode == 3) ? make_sample_key(a.seed, qb, kb, far_bit) : make_key(sc[i], kb, far_bit);
-        w.nhi[i] = selectable ? ~(uint32_t)(key >> 32) : 0u;
-        w.nlo[i] = selectable ? ~(uint32_t)key : 0u;
-        forced |= (uint64_t)(c == 3 ? 1 : 0) << i;
-        n += __popcll(__ballot(selectable));
-        n_near_cnt += __popcll(__ballot(selectable && c == 1));
+        const uint32_t v = (a.mode == 3) ? ~fmix32(seed_row + (uint32_t)kb) : score_image(sc[i]);
+        const bool selectable = __builtin_amdgcn_inverse_ballot_w64(m_sel[i]);
+        const bool far_key = __builtin_amdgcn_inverse_ballot_w64(m_far[i]);
+        const uint32_t hi = (v >> 1) | (far_key ? 0u : 0x80000000u), lo = (v << 31) | (0x7fffffffu ^ (uint32_t)kb);
+        w.c[i] = selectable ? (((uint64_t)hi << 32) | lo) : 0ull;
+        n += __popcll(m_sel[i]);
+        n_far += __popcll(m_far[i]);
     }
     WaveThreshold t_near{0u, 0u}, t_far{0u, 0u};
     int k_near = 0, k_far = 0;
     if (n > 0) {
-        const int n_near = a.two_ratio ? n_near_cnt : n;
+        const int n_near = n - n_far;                               // m_far is empty unless the classes rank apart
         k_near = keep_count(n_near, a.ratio);
-        k_far = a.two_ratio ? keep_count(n - n_near, a.ratio_far) : 0;
-        if (k_near > 0) t_near = kth_smallest_wave<kSlots>(w, k_near, index_bits);
-        if (k_far > 0) t_far = kth_smallest_wave<kSlots>(w, n_near + k_far, index_bits);
+        k_far = a.two_ratio ? keep_count(n_far, a.ratio_far) : 0;
+        uint64_t* list = s_list[wave];
+        if (k_near > 0 && !(k_near <= kShortListMaxK && kth_smallest_wave_short_list<kSlots>(w, k_near, index_bits, list, &t_near)))
+            t_near = kth_smallest_wave<kSlots>(w, k_near, index_bits);
+        const int k_all = n_near + k_far;
+        if (k_far > 0 && !(k_all <= kShortListMaxK && kth_smallest_wave_short_list<kSlots>(w, k_all, index_bits, list, &t_far)))
+            t_far = kth_smallest_wave<kSlots>(w, k_all, index_bits);
     }
+    // a NEAR key's complement has bit 63 set and so has every threshold of the NEAR ranking: no FAR key reaches it;
+    // the FAR ranking's threshold is reached by every NEAR key and by the k_far best FAR keys.  With nothing to rank
+    // the threshold is beyond every key.
+    const uint64_t c_near = k_near > 0 ? (((uint64_t)t_near.hi << 32) | t_near.lo) : ~0ull;
+    const uint64_t c_far = k_far > 0 ? (((uint64_t)t_far.hi << 32) | t_far.lo) : ~0ull;
     int kept = 0;
 #pragma unroll
     for (int i = 0; i < kSlots; ++i) {
-        // a far key has bit 63 set, so its complement has it clear; a word pair of 0 reaches no threshold
-        const bool far_key = (w.nhi[i] >> 31) == 0u;
-        const WaveThreshold t = far_key ? t_far : t_near;
-        const bool ranked = far_key ? k_far > 0 : k_near > 0;
-        const bool sel = ranked && (w.nhi[i] > t.hi || (w.nhi[i] == t.hi && w.nlo[i] >= t.lo));
-        const uint64_t m = __ballot(sel || ((forced >> i) & 1ull));
+        uint64_t m = m_forced[i] | __ballot(w.c[i] >= c_near);
+        if (a.two_ratio) m |= __ballot(w.c[i] >= c_far) & m_far[i];
         kept += __popcll(m);
-        if (lane < 2 && 2 * i + lane < words) keepbits[row * words + 2 * i + lane] = (uint32_t)(m >> (32 * lane));
+        if (lane < 2 && 2 * i + lane < words) keepbits[row * words + 2 * i + lane] = lane ? (uint32_t)(m >> 32) : (uint32_t)m;
     }
     if (lane == 0) counts[row] = kept;
 }
@@ -590,27 +679,39 @@ __global__ __launch_bounds__(kThreads) void k_emit(const uint32_t* __restrict__ 
 
 }  // namespace
 
-hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* class_map, int32_t* row_sel,
-                            unsigned long long* totals, hipStream_t s) {
+// register slots of the selection kernel for a row of Sb key blocks (0: too long for it)
+int wave_select_slots(int Sb) {
+    const int need = (Sb + 63) / 64;
+    for (int s : {2, 4, 8, 12, 16})
+        if (need <= s) return s;
+    return 0;
+}
+static_assert(kWaveSelectMaxSlots == 16, "the largest instantiation");
+
+hipError_t launch_class_map(const Geometry& g, const FrameTab& tab, uint8_t* class_map, uint64_t* class_bits,
+                            int32_t* row_sel, unsigned long long* totals, hipStream_t s) {
     hipLaunchKernelGGL(k_class_map, dim3(g.Sb), dim3(kThreads), 0, s, g, tab, class_map, row_sel, totals);
+    if (class_bits)
+        hipLaunchKernelGGL(k_class_bits, dim3((g.Sb + kWaves - 1) / kWaves), dim3(kThreads), 0, s, class_map, g.Sb,
+                           wave_select_slots(g.Sb), class_bits);
     return hipGetLastError();
 }
 
-hipError_t launch_select(const uint8_t* class_map, const float* scores, int B, int masks, int Sb,
-                         const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s) {
+hipError_t launch_select(const uint8_t* class_map, const uint64_t* class_bits, const float* scores, int B, int masks,
+                         int Sb, const SelectArgs& a, uint32_t* keepbits, int32_t* counts, hipStream_t s) {
     // One wave per row pays when there are more rows than workgroups the chip holds at once (per-head masks), and while
     // a row's keys fit 16 register pairs per lane: measured 15 - 35 % faster than a workgroup per row there, slower
     // beyond 1024 key blocks (registers, one wave per SIMD) and on the few hundred rows of a single fused mask.
     const int64_t rows_total = (int64_t)B * masks * Sb;
-    if ((a.mode == 0 || a.mode == 3) && Sb <= 64 * kWaveSelectMaxSlots && rows_total >= kWaveSelectMinRows) {
+    if ((a.mode == 0 || a.mode == 3) && class_bits && Sb <= kWaveSelectMaxBlocks && rows_total >= kWaveSelectMinRows) {
         const dim3 grid((unsigned)((rows_total + kWaves - 1) / kWaves));
-        const int slots = (Sb + 63) / 64;
+        const int slots = wave_select_slots(Sb);
 #define DR_SELECT_WAVE(S) \
-    hipLaunchKernelGGL(k_select_wave<S>, grid, dim3(kThreads), 0, s, class_map, scores, rows_total, Sb, a, keepbits, counts)
-        if (slots <= 2) DR_SELECT_WAVE(2);
-        else if (slots <= 4) DR_SELECT_WAVE(4);
-        else if (slots <= 8) DR_SELECT_WAVE(8);
-        else if (slots <= 12) DR_SELECT_WAVE(12);
+    hipLaunchKernelGGL(k_select_wave<S>, grid, dim3(kThreads), 0, s, class_bits, scores, rows_total, Sb, a, keepbits, counts)
+        if (slots == 2) DR_SELECT_WAVE(2);
+        else if (slots == 4) DR_SELECT_WAVE(4);
+        else if (slots == 8) DR_SELECT_WAVE(8);
+        else if (slots == 12) DR_SELECT_WAVE(12);
         else DR_SELECT_WAVE(16);
 #undef DR_SELECT_WAVE
         return hipGetLastError();
