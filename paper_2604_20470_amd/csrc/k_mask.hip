@@ -290,7 +290,8 @@ __global__ __launch_bounds__(kThreads) void k_select(const uint8_t* __restrict__
 // per row, k_select holds 8 rows per CU in flight, each waiting on its barriers; this holds up to 32.
 // grid: ceil(B * masks * Sb / 4).
 constexpr int kWaveSelectMaxSlots = kWaveSelectMaxBlocks / 64;
-constexpr int64_t kWaveSelectMinRows = 2048;
+constexpr int64_t kWaveSelectMinRows = 1;
+constexpr int64_t kWaveSelectPackRows = 2048;
 static_assert(kWaveSelectMaxSlots <= 64, "one bit per slot in a 64-bit word");
 
 template <int kSlots>
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(kThreads) void k_select_wave(const uint64_t* __rest
                                                           int32_t* __restrict__ counts) {
     __shared__ uint64_t s_list[kWaves][64];                       // a wave's short list of candidate keys
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t row = (int64_t)blockIdx.x * kWaves + wave;      // the same in every lane, and known to be
+    const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;   // the same in every lane, and known to be
     if (row >= rows_total) return;
     const int qb = (int)(row % Sb);
     const float* srow = scores + row * Sb;
@@ -704,10 +705,12 @@ hipError_t launch_select(const uint8_t* class_map, const uint64_t* class_bits, c
     // beyond 1024 key blocks (registers, one wave per SIMD) and on the few hundred rows of a single fused mask.
     const int64_t rows_total = (int64_t)B * masks * Sb;
     if ((a.mode == 0 || a.mode == 3) && class_bits && Sb <= kWaveSelectMaxBlocks && rows_total >= kWaveSelectMinRows) {
-        const dim3 grid((unsigned)((rows_total + kWaves - 1) / kWaves));
+        // few rows: one per workgroup, so that they spread over as many CUs as there are rows
+        const int waves = rows_total >= kWaveSelectPackRows ? kWaves : 1;
+        const dim3 grid((unsigned)((rows_total + waves - 1) / waves)), block(64 * waves);
         const int slots = wave_select_slots(Sb);
 #define DR_SELECT_WAVE(S) \
-    hipLaunchKernelGGL(k_select_wave<S>, grid, dim3(kThreads), 0, s, class_bits, scores, rows_total, Sb, a, keepbits, counts)
+    hipLaunchKernelGGL(k_select_wave<S>, grid, block, 0, s, class_bits, scores, rows_total, Sb, a, keepbits, counts)
         if (slots == 2) DR_SELECT_WAVE(2);
         else if (slots == 4) DR_SELECT_WAVE(4);
         else if (slots == 8) DR_SELECT_WAVE(8);
@@ -752,7 +755,7 @@ __global__ __launch_bounds__(kThreads) void k_emit_wave(const uint32_t* __restri
                                                         int shared, const int32_t* __restrict__ rowptr,
                                                         int32_t* __restrict__ colidx, int64_t capacity) {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const int64_t r = (int64_t)blockIdx.x * kWaves + wave;      // (mask_id, qb) flattened
+    const int64_t r = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;      // (mask_id, qb) flattened
     if (r >= rows_total) return;
     const int64_t mask_id = r / Sb;
     const int qb = (int)(r - mask_id * Sb);
@@ -776,7 +779,8 @@ hipError_t launch_emit(const uint32_t* keepbits, const int32_t* counts, int B, i
     hipLaunchKernelGGL(k_row_offsets, dim3(masks, B), dim3(kThreads), 0, s, counts, masks, Sb, shared ? 1 : 0, rowptr, nnz);
     if (Sb <= 64 * 32) {
         const int64_t rows_total = (int64_t)B * masks * Sb;
-        hipLaunchKernelGGL(k_emit_wave, dim3((unsigned)((rows_total + kWaves - 1) / kWaves)), dim3(kThreads), 0, s, keepbits,
+        const int waves = rows_total >= kWaveSelectPackRows ? kWaves : 1;
+        hipLaunchKernelGGL(k_emit_wave, dim3((unsigned)((rows_total + waves - 1) / waves)), dim3(64 * waves), 0, s, keepbits,
                            rows_total, Sb, shared ? 1 : 0, rowptr, colidx, capacity);
     } else {
         hipLaunchKernelGGL(k_emit, dim3(Sb, masks, B), dim3(kThreads), 0, s, keepbits, masks, Sb, shared ? 1 : 0, rowptr,
