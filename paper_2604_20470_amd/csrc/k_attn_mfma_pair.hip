@@ -78,8 +78,8 @@ __device__ __forceinline__ void issue_chunk(const LoadPlan& lp, const char* Kh, 
 
 struct State {
     v16f o[2][4];     // [query half][channel block] O^T accumulators (accumulation registers)
-    v16f lacc[2];     // [query half] normaliser: every row of the tile holds the 32 queries' sums (accumulation registers)
-    v8bf ones;        // A operand of the normaliser's matrix instruction
+    v4f lacc[2];      // [query half] normaliser: a 16x16 tile that holds the 32 queries' sums (accumulation registers)
+    v8bf ones;        // A operand of the normaliser's matrix instruction: per lane all 1 or all 0 (sum_selector)
 };
 
 struct ReadPlan {
@@ -97,6 +97,19 @@ typedef __attribute__((address_space(3))) v4s* lds_v4;
 __device__ __forceinline__ void mfma_pv(v16f& acc, const v8bf& a, const v8bf& b) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
+// The normaliser's instruction: the 16x16x32 shape, half the passes of a 32x32x16.  Its B operand is a P^T fragment
+// as the 32x32x16 instructions take it (lane: query lane % 32, eight keys), which the 16x16x32 shape reads as
+// column lane % 16 with the four 16-lane groups as four stretches of its contraction index: groups 0 and 2 hold
+// query n, groups 1 and 3 query n + 16.  An A operand that is 1 in groups 0 and 2 for rows 0..7 and in groups 1 and
+// 3 for rows 8..15, 0 elsewhere (a lane's eight values are all the same), makes row m, column n of the product the
+// fragment's sum for query n (m < 8) or n + 16 (m >= 8): lane L of the result holds the sum of query
+// (L % 16) + 16 * (L / 32), in each of its four registers.
+__device__ __forceinline__ void mfma_l(v4f& acc, const v8bf& a, const v8bf& b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ bool sum_selector(int lane) { return (((lane >> 4) & 1) != 0) == ((lane & 15) >= 8); }
+// the lane that holds the sum of query q (0..31) of a query half
+__device__ __forceinline__ int sum_lane(int q) { return (q & 15) + 32 * (q >> 4); }
 // The logit products go through inline assembly as well, so that the register classes are fixed here: logits in
 // ordinary registers (the exponentials read them), Q fragments in accumulation registers.  The schedule keeps every
 // reader of a logit tile at least one matrix-instruction slot behind the tile's last step.
@@ -111,14 +124,14 @@ __device__ __forceinline__ void mfma_s(v16f& s, const v8bf& k, const v8bf& q) {
 // exact.  (Summing the fp32 exponentials instead is what kernels that subtract the row maximum do, where the
 // dominant probability is exactly 1 and rounds without error; here no reference is subtracted, the dominant
 // probability is 2^s with any mantissa, and its rounding error, up to 2^-8 relative, would go straight into O:
-// 2.2e-2 on rows with one dominant key and |V| near 5.)  The sums are formed by the matrix pipe: one more
-// 32x32x16 instruction per P^T fragment with an all-ones A operand, lacc += 1 P^T, leaves the 32 queries' sums over
-// the fragment's 16 keys in every row of lacc.  That is a quarter more O += V P instructions (72 instead of 64
-// per chunk), but the vector ALU, whose instruction issue is what bounds a lone wavefront, loses three
-// instructions per pair of probabilities (two unpacks, two additions; a lone wavefront pays 5 to 6 cycles for each).
+// 2.2e-2 on rows with one dominant key and |V| near 5.)  The sums are formed by the matrix pipe: one more matrix
+// instruction per P^T fragment (mfma_l: a selector of ones and zeros times P^T) leaves the 32 queries' sums over
+// the fragment's 16 keys in lacc.  That is 72 matrix instructions per chunk instead of 64, eight of them of half
+// length, but the vector ALU, whose instruction issue is what bounds a lone wavefront, loses three instructions per
+// pair of probabilities (two unpacks, two additions; a lone wavefront pays 5 to 6 cycles for each).
 // The accumulators are operands of the wait so that every later read of them depends on it (a plain register copy
 // could otherwise be scheduled right behind the matrix instruction that produces its source).
-__device__ __forceinline__ void drain_mfma(v16f (&o)[2][4], v16f (&lacc)[2]) {
+__device__ __forceinline__ void drain_mfma(v16f (&o)[2][4], v4f (&lacc)[2]) {
     asm volatile("s_nop 15\n\ts_nop 15"
                  : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[0][2]), "+a"(o[0][3]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[1][2]), "+a"(o[1][3]),
                    "+a"(lacc[0]), "+a"(lacc[1])
@@ -272,7 +285,7 @@ __device__ __forceinline__ void run_slots(const ReadPlan& rd, const v8bf (&qf)[2
             constexpr int t = m.idx >> 2, db = m.idx & 3;
             mfma_pv(st.o[m.qh][db], fr.vf[m.mb][t][db], fr.pf[m.mb][m.qh][t]);
         } else {
-            mfma_pv(st.lacc[m.qh], st.ones, fr.pf[m.mb][m.qh][m.idx]);
+            mfma_l(st.lacc[m.qh], st.ones, fr.pf[m.mb][m.qh][m.idx]);
         }
         // ---- LDS reads ----
         if constexpr (slot >= 10 && slot < 18) fr.kf1[slot - 10] = *(lds_v8)(uintptr_t)(rd.k_addr[slot - 10] + kS + 32 * kRowBytes);
@@ -347,7 +360,7 @@ __device__ __forceinline__ void finish_pending(State& st, Frags& fr) {
     for (int idx = 0; idx < 8; ++idx)
         st.o[1][idx & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.vf[1][idx >> 2][idx & 3], fr.pf[1][1][idx >> 2], st.o[1][idx & 3], 0, 0, 0);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) st.lacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.ones, fr.pf[1][1][t], st.lacc[1], 0, 0, 0);
+    for (int t = 0; t < 2; ++t) st.lacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.ones, fr.pf[1][1][t], st.lacc[1], 0, 0, 0);
 }
 
 // One whole chunk by plain code (no pipelining), from the tiles at LDS addresses rd + stage_off: window rows below
@@ -389,7 +402,7 @@ __device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_o
                     st.o[qh][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.v, pf[t], st.o[qh][db], 0, 0, 0);
                 }
 #pragma unroll
-            for (int t = 0; t < 2; ++t) st.lacc[qh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(st.ones, pf[t], st.lacc[qh], 0, 0, 0);
+            for (int t = 0; t < 2; ++t) st.lacc[qh] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.ones, pf[t], st.lacc[qh], 0, 0, 0);
         }
 }
 
@@ -471,14 +484,14 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) st.lacc[qh][j] = 0.f;
+        for (int j = 0; j < 4; ++j) st.lacc[qh][j] = 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int j = 0; j < 16; ++j) st.o[qh][db][j] = 0.f;
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) st.ones[i] = (__bf16)1.0f;
+    for (int i = 0; i < 8; ++i) st.ones[i] = (__bf16)(sum_selector(lane) ? 1.0f : 0.0f);
     asm volatile("" : "+v"(st.ones));
     DR_PIN_O();
 
@@ -597,7 +610,7 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
     bool out_of_range = false;
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
-        const float l = st.lacc[qh][0];          // every row of the tile holds the sums: lane -> query l32, both halves
+        const float l = __shfl(st.lacc[qh][0], sum_lane(l32));   // lane -> query l32, both halves
         const float inv = (l > 0.f) ? 1.0f / l : 0.f;
         const int qrow = q_wave0 + qh * 32 + l32;
         if (has_rows && qrow < N) {
