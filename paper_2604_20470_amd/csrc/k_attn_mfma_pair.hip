@@ -36,7 +36,7 @@
 // limit nothing overflows (fp32 and bf16 share one exponent range, so large or small probabilities lose no
 // precision), the logit accumulation starts from the constant 0, and the accumulators, which are out of the vector
 // ALU's reach, never need rescaling.  The normaliser sums the probabilities as rounded to bf16 (by one more matrix
-// instruction per P^T fragment, with an all-ones A operand).
+// instruction per P^T fragment, of half length, with a constant operand of ones and zeros).
 #include "attn_mfma_common.h"
 #include "dr_internal.h"
 
