@@ -259,7 +259,7 @@ def main():
         "dense_equivalent_tflops": round(dense_flop / (ms_attn * 1e-3) / 1e12, 1),
         "pct_bf16_mfma_peak": round(100.0 * eff_tflops / PEAK_BF16_TFLOPS, 2),
         "paper_context": "paper reports 1.7x-2.5x end-to-end speedup at >80% sparsity on NVIDIA H100 (not comparable)",
-        "roofline": {"kernel": ({128: "k_attn_mfma_pair", 64: "k_attn_mfma_quad", 32: "k_attn_mfma_bs32"}[wl.Bs]
+        "roofline": {"kernel": ({128: "k_attn_mfma_pair", 64: "k_attn_mfma_quad", 32: "k_attn_mfma_oct"}[wl.Bs]
                                 if (wl.dtype == "bf16" and wl.d == 128) else "k_attn_generic"), "bound": "mfma", "achieved": round(eff_tflops, 1),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(eff_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": read_traffic(f"k_attn_mfma_pair_{args.config}") if wl.Bs == 128 else None,

@@ -226,11 +226,12 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
  * was written), neither is reported; a row
  * whose list is not ascending is still summed correctly (softmax does not depend on the order).
  * A key block listed twice in one row is outside the contract (the paths that merge lists count
- * it once, the others once per listing).  For block size 32 the call first merges the rows
- * of each group of 128 query tokens into one key-block list; for block sizes 128 and 64 (bf16,
- * d = 128, N >= 64) it merges the rows of every two (four) adjacent query blocks, 256 queries,
- * which one workgroup then walks together (environment variable DR_ATTN_PAIRS=0, read when the
- * context is created, keeps one workgroup per 128 query rows instead).  The merged lists live in
+ * it once, the others once per listing).  For bf16, d = 128 and N >= 64 the call first merges
+ * the rows of every two (block size 128), four (64) or eight (32) adjacent query blocks, 256
+ * queries, into one key-block list, which one workgroup then walks (block size 32: fewer than
+ * 2^24 blocks; environment variable DR_ATTN_PAIRS=0, read when the context is created, keeps one
+ * workgroup per 128 query rows instead, which for the block sizes 64 and 32 walks the merged
+ * rows of those 128 queries).  The merged lists live in
  * context-owned device scratch of the size of the colidx arrays the call is given
  * (B * mask_heads * colidx_stride entries), grown on demand: DR_ERR_NOMEM if that allocation fails.
  * Argument errors (NULL or misaligned pointers, strides, mask_heads) are rejected on the host

@@ -554,11 +554,12 @@ dr_status attn_prepare(dr_ctx* ctx, const dr_shape* shape, const void* Q, const 
     return DR_OK;
 }
 
-// Block sizes 128 and 64: the 256 queries of two (four) adjacent query blocks walk the union of their rows, one
-// wavefront per SIMD; rows that kernel flags are taken again by the second pass of the kernels with one 128-row group
+// The 256 queries of two (block size 128), four (64) or eight (32) adjacent query blocks walk the union of their rows,
+// one wavefront per SIMD; rows that kernel flags are taken again by the second pass of the kernels with one 128-row group
 // per workgroup.
 bool attn_wants_pairs(const dr_ctx* ctx, const AttnArgs& a) {
-    return ctx->attn_pairs && a.bf16 && a.td.d == 128 && (a.Bs == 128 || a.Bs == 64) && a.td.N >= 64 && a.Sb < (1 << 28);
+    return ctx->attn_pairs && a.bf16 && a.td.d == 128 && (a.Bs == 128 || a.Bs == 64 || a.Bs == 32) && a.td.N >= 64 &&
+           a.Sb < (a.Bs == 32 ? (1 << 24) : (1 << 28));
 }
 
 dr_status attn_launch(dr_ctx* ctx, const AttnArgs& a, bool pairs, hipStream_t s) {

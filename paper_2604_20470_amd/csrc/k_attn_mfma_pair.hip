@@ -1,5 +1,6 @@
-// Stage (c), MFMA path for bf16, d = 128, Bs = 128 (paper Eqs. 12-13 with epsilon -> 0): the variant that walks
-// PAIRS of adjacent query blocks.  gfx950 (CDNA4) only.
+// Stage (c), MFMA path for bf16, d = 128 (paper Eqs. 12-13 with epsilon -> 0): the variant that walks 256 queries
+// per workgroup -- PAIRS of adjacent query blocks at Bs = 128 (described here), four blocks at Bs = 64, eight at
+// Bs = 32 (the differences are noted at the kernels' definitions below).  gfx950 (CDNA4) only.
 //
 // One workgroup = 4 wavefronts x 64 queries = query blocks 2p and 2p + 1 of one (batch, head); one wavefront per
 // SIMD, so that each may use the whole register file: the 128 O^T accumulators of its 64 queries live in the
@@ -73,6 +74,20 @@ __device__ __forceinline__ void issue_chunk(const LoadPlan& lp, const char* Kh, 
     for (int i = 0; i < 4; ++i) {
         dma16(lp.koff_i[i], kbase, m0 + i * 4096);
         dma16(lp.voff_i[i], vbase, m0 + kTileBytes + i * 4096);
+    }
+}
+
+// The same for a chunk made of two 32-row windows (block size 32): tile rows 0..31 from key0_a, rows 32..63 from key0_b.
+// The per-lane offsets of pieces 2, 3 already contain their 32 rows: the second base is taken 32 rows back.
+template <int STAGE>
+__device__ __forceinline__ void issue_chunk2(const LoadPlan& lp, const char* Kh, const char* Vh, int key0_a, int key0_b, int64_t row_bytes) {
+    const uint64_t ka = uniform64((uint64_t)(Kh + (int64_t)key0_a * row_bytes)), va = uniform64((uint64_t)(Vh + (int64_t)key0_a * row_bytes));
+    const uint64_t kb = uniform64((uint64_t)(Kh + ((int64_t)key0_b - 32) * row_bytes)), vb = uniform64((uint64_t)(Vh + ((int64_t)key0_b - 32) * row_bytes));
+    const uint32_t m0 = lp.m0_k + STAGE * kStageBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        dma16(lp.koff_i[i], i < 2 ? ka : kb, m0 + i * 4096);
+        dma16(lp.voff_i[i], i < 2 ? va : vb, m0 + kTileBytes + i * 4096);
     }
 }
 
@@ -188,6 +203,9 @@ struct Frags {
     v8bf pf[2][2][2];      // [mb][qh][t]
     v16f s[2][2];          // [mb][qh]
     float e_pair[2];       // the pair of exponentials in flight: packed in the slot after the second was taken
+    // block size 32 only: all-ones where the wavefront's query block qh lists the key block of key half mb, else 0 (the
+    // probabilities of such a tile are packed as 0); tm11_prev: the same for tile (1,1) of the chunk still in flight
+    uint32_t tm[2][2], tm11_prev;
 };
 
 template <int I, int E, class F>
@@ -219,9 +237,39 @@ struct Next {
     int key0;                         // first row of the 64-row window
     uint64_t off, kbase, vbase;
     bool own;                         // the wave's query block lists the key block
+    // block size 32 (a chunk = two list entries = two 32-row windows; the wave has two query blocks, bits 2 grp, 2 grp + 1)
+    int n_ent;                        // entries the chunk loop walks
+    uint32_t e2;                      // second entry (owner bits cleared when there is none)
+    int key0_b;
+    uint64_t off_b, kbase2, vbase2;   // second window, 32 rows back (see issue_chunk2)
+    uint32_t own4;                    // bit mb * 2 + qh
 };
 template <int K, int BS>
 __device__ __forceinline__ void next_step(Next& nx) {
+    if constexpr (BS == 32) {
+        if constexpr (K == 0) {
+            nx.e = (uint32_t)__builtin_amdgcn_readlane(nx.win, (2 * nx.c2) & 63);
+            const uint32_t e2 = (uint32_t)__builtin_amdgcn_readlane(nx.win, (2 * nx.c2 + 1) & 63);
+            nx.e2 = (2 * nx.c2 + 1 < nx.n_ent) ? e2 : (nx.e & 0x00ffffffu);
+        }
+        if constexpr (K == 1) {
+            // (the clamps never act on a list as k_group_union writes it; they keep any other list inside K / V)
+            nx.key0 = min(min((int)(nx.e & 0x00ffffffu), nx.Sb - 1) * 32, nx.N - 32);
+            nx.key0_b = min(min((int)(nx.e2 & 0x00ffffffu), nx.Sb - 1) * 32, nx.N - 32);
+        }
+        if constexpr (K == 2) {
+            nx.own4 = ((nx.e >> (24 + 2 * nx.grp)) & 3u) | (((nx.e2 >> (24 + 2 * nx.grp)) & 3u) << 2);
+            nx.own = nx.own4 != 0u;
+            nx.off = (uint64_t)(uint32_t)nx.key0 * nx.row_bytes;
+            nx.off_b = (uint64_t)(uint32_t)nx.key0_b * nx.row_bytes - 32ull * nx.row_bytes;
+        }
+        if constexpr (K == 3) nx.kbase = uniform64((uint64_t)nx.Kh + nx.off);
+        if constexpr (K == 4) nx.vbase = uniform64((uint64_t)nx.Vh + nx.off);
+        if constexpr (K == 5) nx.kbase2 = uniform64((uint64_t)nx.Kh + nx.off_b);
+        if constexpr (K == 6) nx.vbase2 = uniform64((uint64_t)nx.Vh + nx.off_b);
+        return;
+    }
+    if constexpr (K > 4) return;
     constexpr int kSh = BS == 128 ? 1 : 0;      // chunks per list entry, as a shift
     if constexpr (K == 0) nx.e = (uint32_t)__builtin_amdgcn_readlane(nx.win, (nx.c2 >> kSh) & 63);
     if constexpr (K == 1) {
@@ -263,7 +311,7 @@ __device__ __forceinline__ void run_slots(const ReadPlan& rd, const v8bf (&qf)[2
     static_for<FROM, TO>([&](auto slot_c) {
         constexpr int slot = decltype(slot_c)::value;
         constexpr MfmaSlot m = mfma_at(slot);
-        if constexpr (!kSkip && slot >= 28 && slot < 33) next_step<slot - 28, BS>(nx);
+        if constexpr (!kSkip && slot >= 28 && slot < 35) next_step<slot - 28, BS>(nx);
         if constexpr (!kSkip) {
             // K fragments of key half 0 (read in slots 60..67 of the previous chunk); of key half 1 (slots 10..17: at most
             // the 16 V^T reads behind them are still out); V^T of key half 0 (18..25); of key half 1 (44..51: only
@@ -313,6 +361,14 @@ __device__ __forceinline__ void run_slots(const ReadPlan& rd, const v8bf (&qf)[2
                 v2bf pk;
                 pk[0] = (__bf16)fr.e_pair[0];
                 pk[1] = (__bf16)fr.e_pair[1];
+                if constexpr (BS == 32) {
+                    // the pairs of tile (1,1) packed in slots 0..8 belong to the chunk before
+                    constexpr bool prev = slot == 0 || (pe.mb == 1 && pe.qh == 1 && pe.gi >= 4);
+                    union { v2bf v; uint32_t u; } b;
+                    b.v = pk;
+                    b.u &= prev ? fr.tm11_prev : fr.tm[pe.mb][pe.qh];
+                    pk = b.v;
+                }
                 asm volatile("" : "+v"(pk));      // anchors the pack in this slot of the interleaved stream
                 fr.pf[pe.mb][pe.qh][t][i] = pk[0];
                 fr.pf[pe.mb][pe.qh][t][i + 1] = pk[1];
@@ -325,12 +381,14 @@ __device__ __forceinline__ void run_slots(const ReadPlan& rd, const v8bf (&qf)[2
         if constexpr (slot >= 56 && slot < 64 && TO == kSlots) {
             // the barrier has released the stage: one tile load each of the chunk after next
             constexpr int i = (slot - 56) >> 1;
+            constexpr bool second = BS == 32 && i >= 2;      // block size 32: tile rows 32..63 come from the second window
+            const uint64_t kb_i = second ? nx.kbase2 : nx.kbase, vb_i = second ? nx.vbase2 : nx.vbase;
             if constexpr (kSkip) {
-                if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], nx.kbase, m0_next + kS + i * 4096);
-                else dma16(lp.voff_i[i], nx.vbase, m0_next + kS + kTileBytes + i * 4096);
+                if constexpr ((slot & 1) == 0) dma16(lp.koff_i[i], kb_i, m0_next + kS + i * 4096);
+                else dma16(lp.voff_i[i], vb_i, m0_next + kS + kTileBytes + i * 4096);
             } else {
-                if constexpr ((slot & 1) == 0) dma16_go(lp.koff_i[i], nx.kbase);
-                else dma16_go(lp.voff_i[i], nx.vbase);
+                if constexpr ((slot & 1) == 0) dma16_go(lp.koff_i[i], kb_i);
+                else dma16_go(lp.voff_i[i], vb_i);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -340,11 +398,22 @@ __device__ __forceinline__ void run_slots(const ReadPlan& rd, const v8bf (&qf)[2
 // Completes what the last chunk leaves in flight: the second half of its tile (1,1), then that tile's O += V P and
 // normaliser (the compiler's own matrix instructions here: outside the hand-scheduled loop it looks after the wait
 // states between matrix instructions and their neighbours).
+template <int BS>
 __device__ __forceinline__ void finish_pending(State& st, Frags& fr) {
+    auto masked = [&](v2bf pk) -> v2bf {
+        if constexpr (BS == 32) {
+            union { v2bf v; uint32_t u; } b;
+            b.v = pk;
+            b.u &= fr.tm11_prev;
+            return b.v;
+        }
+        return pk;
+    };
     {   // the pair whose second exponential was taken in the last slot: values 6, 7 of the first fragment
         v2bf pk;
         pk[0] = (__bf16)fr.e_pair[0];
         pk[1] = (__bf16)fr.e_pair[1];
+        pk = masked(pk);
         fr.pf[1][1][0][6] = pk[0];
         fr.pf[1][1][0][7] = pk[1];
     }
@@ -353,6 +422,7 @@ __device__ __forceinline__ void finish_pending(State& st, Frags& fr) {
         v2bf pk;
         pk[0] = (__bf16)__builtin_amdgcn_exp2f(fr.s[1][1][2 * gi]);
         pk[1] = (__bf16)__builtin_amdgcn_exp2f(fr.s[1][1][2 * gi + 1]);
+        pk = masked(pk);
         fr.pf[1][1][1][(2 * gi) & 7] = pk[0];
         fr.pf[1][1][1][((2 * gi) & 7) + 1] = pk[1];
     }
@@ -366,12 +436,13 @@ __device__ __forceinline__ void finish_pending(State& st, Frags& fr) {
 // One whole chunk by plain code (no pipelining), from the tiles at LDS addresses rd + stage_off: window rows below
 // `lo` masked.  Used before the pipelined loop for the sequence's partial chunk.
 __device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_off, const v8bf (&qf)[2][8], State& st,
-                                            int lo, int half) {
+                                            int lo, int half, uint32_t qh_mask) {
     constexpr uint32_t kV = kTileBytes;
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
+            if (!((qh_mask >> qh) & 1u)) continue;      // (block size 32: a wave's two query halves are two query blocks)
             v16f acc;
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[j] = 0.f;
@@ -411,8 +482,10 @@ __device__ __forceinline__ void plain_chunk(const ReadPlan& rd, uint32_t stage_o
 // 2p + 1; BS = 64: wave w block 4p + w).
 template <int BS>
 __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
-    constexpr int kL = kRowsPerItem / BS;       // query blocks per workgroup: 2 (waves 0-1, 2-3) or 4 (one per wave)
-    constexpr int kSh = BS == 128 ? 1 : 0;      // chunks per list entry, as a shift
+    constexpr int kL = kRowsPerItem / BS;       // query blocks per workgroup: 2 (waves 0-1, 2-3), 4 (one per wave) or 8 (two per wave)
+    constexpr int kSh = BS == 128 ? 1 : 0;      // chunks per list entry, as a shift (block size 32: two entries per chunk)
+    constexpr int kOwnShift = BS == 32 ? 24 : 28;               // an entry: key block below, owner bits from here
+    constexpr uint32_t kKbMask = (1u << kOwnShift) - 1u;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int half = lane >> 5, l32 = lane & 31;
@@ -423,9 +496,11 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
     const int item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     if (item >= total_items) return;
     const int pair = item % n_pairs, h = (item / n_pairs) % a.td.H, b = item / (n_pairs * a.td.H);
+    // grp: the wave's owner bit in a list entry (block size 32: its two bits are 2 grp and 2 grp + 1)
     const int grp = BS == 128 ? wave >> 1 : wave;
-    const bool has_rows = kL * pair + grp < a.Sb;
-    const int qb = min(kL * pair + grp, a.Sb - 1);
+    const int qb_first = BS == 32 ? kL * pair + 2 * wave : kL * pair + grp;      // the wave's (first) query block, not clamped
+    const bool has_rows = qb_first < a.Sb;
+    const int qb = min(qb_first, a.Sb - 1);
     const int N = a.td.N;
     const int64_t row_bytes = a.td.stride_n * 2;
     const int64_t head_off = ((int64_t)b * a.td.stride_b + (int64_t)h * a.td.stride_h) * 2;
@@ -441,7 +516,7 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
     const int cnt = __builtin_amdgcn_readfirstlane(a.gcount[mask_id * n_pairs + pair]);
 
     const float cs = kExpScale;
-    const int q_wave0 = BS == 128 ? qb * 128 + (wave & 1) * 64 : qb * 64;
+    const int q_wave0 = BS == 128 ? qb * 128 + (wave & 1) * 64 : qb * BS;
     v8bf qf[2][8];
 #pragma unroll
     for (int qh = 0; qh < 2; ++qh) {
@@ -501,7 +576,7 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
     // last 64 rows (its leading 64 - n_last % 64 rows masked).  The list is ascending, so only its last entry can be
     // that block. ----
     const int n_last = N - (a.Sb - 1) * BS;
-    const int part_keys = n_last % kChunkKeys;
+    const int part_keys = n_last % (BS == 32 ? 32 : kChunkKeys);
     int wbase = 0;
     int win = (cnt > 0) ? gl[min(lane, cnt - 1)] : 0;
     const uint32_t e_last = (cnt > 0) ? (uint32_t)gl[cnt - 1] : 0u;
@@ -514,32 +589,60 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
         for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(qf[qh][ks]));
     asm volatile("" : "+v"(win));
     const uint32_t e_last_s = __builtin_amdgcn_readfirstlane(e_last);
-    const bool has_last = cnt > 0 && (int)(e_last_s & 0x0fffffffu) >= a.Sb - 1;
-    const int n_chunks = (cnt << kSh) - (has_last ? (1 << kSh) - n_last / kChunkKeys : 0);     // full chunks, in list order
+    const bool has_last = cnt > 0 && (int)(e_last_s & kKbMask) >= a.Sb - 1;
     const bool has_part = has_last && part_keys != 0;
-    const bool own_part = ((e_last_s >> (28 + grp)) & 1u) != 0;
-    struct Desc { int key0; bool own; };
-    auto describe = [&](int c) -> Desc {          // c < n_chunks, its entry inside the register window
-        const uint32_t e = (uint32_t)__builtin_amdgcn_readlane(win, (c >> kSh) & 63);
-        const int kb = min((int)(e & 0x0fffffffu), a.Sb - 1);
-        // (the clamp never acts on a list as k_group_union writes it; it keeps any other list inside K / V)
-        return Desc{min(kb * BS + (c & kSh) * kChunkKeys, N - kChunkKeys), ((e >> (28 + grp)) & 1u) != 0};
+    // Block size 32: the loop walks the entries two at a time (n_ent of them: all but a partial last key block, which
+    // is taken before the loop like the partial chunk of the larger block sizes: its keys are the last part_keys rows
+    // of the window of the sequence's last 64 rows).
+    const int n_ent = cnt - ((BS == 32 && has_part) ? 1 : 0);
+    const int n_chunks = BS == 32 ? (n_ent + 1) >> 1
+                                  : (cnt << kSh) - (has_last ? (1 << kSh) - n_last / kChunkKeys : 0);     // full chunks, in list order
+    // the query halves (block size 32: query blocks) of this wave that list the partial block
+    const uint32_t own_part = BS == 32 ? (e_last_s >> (kOwnShift + 2 * grp)) & 3u
+                                       : (((e_last_s >> (kOwnShift + grp)) & 1u) ? 3u : 0u);
+    struct Desc { int key0, key0_b; uint32_t own4; bool own; };
+    auto describe = [&](int c) -> Desc {          // c < n_chunks, its entries inside the register window
+        // (the clamps never act on a list as k_group_union writes it; they keep any other list inside K / V)
+        if constexpr (BS == 32) {
+            const uint32_t e = (uint32_t)__builtin_amdgcn_readlane(win, (2 * c) & 63);
+            const uint32_t e2r = (uint32_t)__builtin_amdgcn_readlane(win, (2 * c + 1) & 63);
+            const uint32_t e2 = (2 * c + 1 < n_ent) ? e2r : (e & kKbMask);
+            const uint32_t own4 = ((e >> (kOwnShift + 2 * grp)) & 3u) | (((e2 >> (kOwnShift + 2 * grp)) & 3u) << 2);
+            return Desc{min(min((int)(e & kKbMask), a.Sb - 1) * 32, N - 32), min(min((int)(e2 & kKbMask), a.Sb - 1) * 32, N - 32),
+                        own4, own4 != 0u};
+        } else {
+            const uint32_t e = (uint32_t)__builtin_amdgcn_readlane(win, (c >> kSh) & 63);
+            const int kb = min((int)(e & kKbMask), a.Sb - 1);
+            const bool own = ((e >> (kOwnShift + grp)) & 1u) != 0;
+            return Desc{min(kb * BS + (c & kSh) * kChunkKeys, N - kChunkKeys), 0, own ? 15u : 0u, own};
+        }
+    };
+    auto issue = [&](auto stage_c, const Desc& d) {
+        constexpr int stage = decltype(stage_c)::value;
+        if constexpr (BS == 32) issue_chunk2<stage>(lp, Kh, Vh, d.key0, d.key0_b, row_bytes);
+        else issue_chunk<stage>(lp, Kh, Vh, d.key0, row_bytes);
+    };
+    auto tile_masks = [](Frags& fr, uint32_t own4) {          // block size 32: own4 bit mb * 2 + qh
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int qh = 0; qh < 2; ++qh) fr.tm[mb][qh] = ((own4 >> (mb * 2 + qh)) & 1u) ? ~0u : 0u;
     };
 
     if (n_chunks > 0 || has_part) {
         // stage 0: the first full chunk (or, without one, the partial chunk); stage 1: the partial chunk
-        const Desc d0 = (n_chunks > 0) ? describe(0) : Desc{N - kChunkKeys, false};
-        issue_chunk<0>(lp, Kh, Vh, d0.key0, row_bytes);
+        const Desc d0 = (n_chunks > 0) ? describe(0) : Desc{N - kChunkKeys, N - 32, 0u, false};
+        issue(std::integral_constant<int, 0>{}, d0);
         if (has_part) issue_chunk<1>(lp, Kh, Vh, N - kChunkKeys, row_bytes);
         DR_WAIT_VMCNT0();
         DR_BARRIER();
         if (has_part) {
-            if (own_part) plain_chunk(rd, kStageBytes, qf, st, kChunkKeys - part_keys, half);
+            if (own_part) plain_chunk(rd, kStageBytes, qf, st, kChunkKeys - part_keys, half, own_part);
             DR_BARRIER();          // stage 1 is free again
         }
         if (n_chunks > 0) {
             const Desc d1 = describe(min(1, n_chunks - 1));
-            issue_chunk<1>(lp, Kh, Vh, d1.key0, row_bytes);          // with a single chunk: that chunk again, never read
+            issue(std::integral_constant<int, 1>{}, d1);          // with a single chunk: that chunk again, never read
             Frags fr;
             // software-pipeline prologue: "previous chunk" = nothing (logits -inf, probabilities and V fragments 0)
 #pragma unroll
@@ -554,6 +657,8 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
                     for (int i = 0; i < 8; ++i) fr.vf[1][t][db][i] = (__bf16)0.f;
             }
             fr.e_pair[0] = fr.e_pair[1] = 0.f;
+            fr.tm11_prev = 0u;
+            uint32_t own4_cur = d0.own4, own4_nxt = d1.own4;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) fr.kf0[ks] = *(lds_v8)(uintptr_t)(rd.k_addr[ks]);
             // Loop invariant at the top of a chunk: its tiles are complete in LDS for every wave, the K fragments of
@@ -562,6 +667,7 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
             bool own_cur = d0.own, own_nxt = d1.own;
             Next nx;
             nx.Sb = a.Sb; nx.N = N; nx.grp = grp; nx.row_bytes = (uint32_t)row_bytes; nx.Kh = Kh; nx.Vh = Vh;
+            nx.n_ent = n_ent; nx.own4 = 0u;
             // The loop takes two chunks per turn, one per LDS stage, so that the stage is a compile-time offset of every
             // read; an odd count is made even by a last chunk that every wavefront sits out.
             const int n_even = (n_chunks + 1) & ~1;
@@ -569,8 +675,9 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
             {                                                                                                           \
                 DR_PIN_O();                                                                                             \
                 nx.c2 = min((C) + 2, n_chunks - 1);                                                                     \
-                const bool refill = (nx.c2 >> kSh) >= wbase + 64;                                                       \
+                const bool refill = (BS == 32 ? 2 * nx.c2 : nx.c2 >> kSh) >= wbase + 64;                                \
                 if (own_cur) {                                                                                          \
+                    if constexpr (BS == 32) tile_masks(fr, own4_cur);                                                   \
                     run_slots<0, 27, false, STAGE, BS>(rd, qf, st, fr, lp, nx);                                             \
                     if (refill) { wbase += 64; win = gl[min(wbase + lane, cnt - 1)]; asm volatile("" : "+v"(win)); }   \
                     nx.win = win;                                                                                       \
@@ -579,10 +686,12 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
                     DR_BARRIER();                                                                                       \
                     __builtin_amdgcn_sched_barrier(0);                                                                  \
                     run_slots<kBarrierSlot, kSlots, false, STAGE, BS>(rd, qf, st, fr, lp, nx);                              \
+                    if constexpr (BS == 32) fr.tm11_prev = fr.tm[1][1];                                                 \
                 } else {                                                                                                \
                     if (refill) { wbase += 64; win = gl[min(wbase + lane, cnt - 1)]; asm volatile("" : "+v"(win)); }   \
                     nx.win = win;                                                                                       \
                     next_step<0, BS>(nx); next_step<1, BS>(nx); next_step<2, BS>(nx); next_step<3, BS>(nx); next_step<4, BS>(nx);           \
+                    next_step<5, BS>(nx); next_step<6, BS>(nx);                                                         \
                     DR_WAIT_VMCNT0();                                                                                   \
                     DR_BARRIER();                                                                                       \
                     __builtin_amdgcn_sched_barrier(0);                                                                  \
@@ -591,6 +700,8 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
                 DR_PIN_O();                                                                                             \
                 own_cur = own_nxt && (C) + 1 < n_chunks;                                                                \
                 own_nxt = nx.own;                                                                                       \
+                own4_cur = own4_nxt;                                                                                    \
+                own4_nxt = nx.own4;                                                                                     \
             }
             asm volatile("; chunk loop begin");      // (markers for the check of the generated code: nothing
             for (int c = 0; c < n_even; c += 2) {    // between them may touch an accumulation register except the
@@ -599,7 +710,7 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
             }
             asm volatile("; chunk loop end");
 #undef DR_CHUNK
-            finish_pending(st, fr);
+            finish_pending<BS>(st, fr);
         }
         DR_WAIT_VMCNT0();          // the loads issued by the last chunks write LDS: none may outlive the workgroup
     }
@@ -628,7 +739,8 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
                 a.lse[((int64_t)b * a.td.H + h) * N + qrow] =
                     (l > 0.f) ? logf(l) : -INFINITY;
             // a row that lists keys has l > 0 unless every exponential underflowed; l = 0 with an empty row is exact
-            const bool listed = rp[qb + 1] > rp[qb];
+            const int qb_h = BS == 32 ? min(qb_first + qh, a.Sb - 1) : qb;      // the query block of this half
+            const bool listed = rp[qb_h + 1] > rp[qb_h];
             if (listed && !(l >= kSumMin && l <= kSumMax && fabsf(__log2f(l)) <= kExactLimit)) out_of_range = true;
         }
     }
@@ -636,7 +748,7 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
     // indexed by 128-row group, four words each.  A wave whose query block lies past the end of the sequence still
     // clears its words when its group exists (block size 64, odd block count): the second pass reads all four.
     const int groups128 = (N + 127) / 128;
-    const int q0_own = (kL * pair + grp) * BS + (BS == 128 ? (wave & 1) * 64 : 0);      // not clamped
+    const int q0_own = qb_first * BS + (BS == 128 ? (wave & 1) * 64 : 0);      // the wave's first query row, not clamped
     if (a.flags && (q0_own >> 7) < groups128) {
         const int any = (has_rows && __any(out_of_range)) ? 1 : 0;
         const int64_t base = (((int64_t)b * a.td.H + h) * groups128 + (q0_own >> 7)) * 4 + ((q0_own >> 6) & 1) * 2;
@@ -648,12 +760,17 @@ __device__ __forceinline__ void attn_pair_body(const AttnArgs& a) {
 // query blocks, one per wavefront, an entry is one chunk; the same 256 queries and the same code otherwise.
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_pair(AttnArgs a) { attn_pair_body<128>(a); }
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_quad(AttnArgs a) { attn_pair_body<64>(a); }
+// Block size 32: eight query blocks, two per wavefront (one per query half); a chunk is two entries of the merged list,
+// its two key halves come from two 32-row windows, and a 32 x 32 tile whose query block does not list the key block of
+// its key half contributes probabilities of 0 (they are masked where they are packed to bf16).
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_attn_mfma_oct(AttnArgs a) { attn_pair_body<32>(a); }
 
 }  // namespace
 
 bool attn_mfma_pair_supported(const AttnArgs& a) {
     // every chunk is a full 64-row window: the sequence must hold one; the 32-bit per-lane offsets must cover it
-    return a.bf16 && a.td.d == kD && (a.Bs == 128 || a.Bs == 64) && a.td.N >= kChunkKeys && a.Sb < (1 << 28) &&
+    return a.bf16 && a.td.d == kD && (a.Bs == 128 || a.Bs == 64 || a.Bs == 32) && a.td.N >= kChunkKeys &&
+           a.Sb < (a.Bs == 32 ? (1 << 24) : (1 << 28)) &&
            a.td.stride_n * 2 * kChunkKeys < (1ll << 31) && a.gcol && a.gcount && a.flags;
 }
 
@@ -662,7 +779,7 @@ hipError_t launch_attn_mfma_pair(const AttnArgs& a, hipStream_t s) {
     const int L = kRowsPerItem / a.Bs;
     hipError_t e = launch_group_union(L, a, s);
     if (e != hipSuccess) return e;
-    auto kern = a.Bs == 128 ? k_attn_mfma_pair : k_attn_mfma_quad;
+    auto kern = a.Bs == 128 ? k_attn_mfma_pair : a.Bs == 64 ? k_attn_mfma_quad : k_attn_mfma_oct;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     const int total = ((a.Sb + L - 1) / L) * a.td.H * a.td.B;

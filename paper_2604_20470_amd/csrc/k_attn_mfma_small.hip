@@ -432,8 +432,8 @@ __device__ __forceinline__ void attn_small_body(const AttnArgs& a) {
 }
 
 // Pre-pass: the ascending union of the L consecutive CSR rows of every group (L = 128 / Bs for the kernels of this
-// file, L = 2 for the kernel that walks pairs of 128-row query blocks), one entry per key block with the
-// set of rows that list it in the top four bits.  A group's entries are written at the colidx offset of its first row
+// file, L = 256 / Bs for the kernels that walk 256 queries per workgroup), one entry per key block with the
+// set of rows that list it in the top four bits (L = 8: the top eight).  A group's entries are written at the colidx offset of its first row
 // (the union is never longer than the rows together), its length to gcount.  Indices are clamped to [0, Sb); an
 // index listed twice in a row counts once.
 // grid: (groups, mask_heads, B).  LDS: L * words presence bitmaps.
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256) void k_group_union(const int32_t* __restrict__
             uint32_t rows = 0;
 #pragma unroll
             for (int l = 0; l < L; ++l) rows |= ((r[l] >> bit) & 1u) << l;
-            if (posn < room) out[posn] = (int32_t)((uint32_t)(wi * 32 + bit) | (rows << 28));
+            if (posn < room) out[posn] = (int32_t)((uint32_t)(wi * 32 + bit) | (rows << (L > 4 ? 24 : 28)));
             ++posn;
         }
         base += total;
@@ -537,11 +537,14 @@ hipError_t launch_small(Kern kern, Kern kern_exact, const AttnArgs& a, hipStream
 }  // namespace
 
 hipError_t launch_group_union(int L, const AttnArgs& a, hipStream_t s) {
-    if ((L != 2 && L != 4) || !a.gcol || !a.gcount) return hipErrorInvalidValue;
+    if ((L != 2 && L != 4 && L != 8) || !a.gcol || !a.gcount) return hipErrorInvalidValue;
+    if (a.Sb >= (L > 4 ? (1 << 24) : (1 << 28))) return hipErrorInvalidValue;      // the key block must fit below the owner bits
     const int groups = (a.Sb + L - 1) / L;
     const size_t lds = (size_t)L * ((a.Sb + 31) / 32) * 4;
     const dim3 grid(groups, a.mask_heads, a.td.B);
-    if (L == 4)
+    if (L == 8)
+        hipLaunchKernelGGL(k_group_union<8>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);
+    else if (L == 4)
         hipLaunchKernelGGL(k_group_union<4>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);
     else
         hipLaunchKernelGGL(k_group_union<2>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);

@@ -82,8 +82,8 @@ def test_hand_scheduled_attention_kernel_compiles_without_spills_or_accumulator_
                             "--cuda-device-only", src, "-o", asm], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr[-2000:]
         reports = [blk for blk in r.stderr.split("Function Name:")[1:]
-                   if "k_attn_mfma_pairE" in blk.splitlines()[0] or "k_attn_mfma_quadE" in blk.splitlines()[0]]
-        assert len(reports) == 2                      # block size 128 and block size 64
+                   if any(k in blk.splitlines()[0] for k in ("k_attn_mfma_pairE", "k_attn_mfma_quadE", "k_attn_mfma_octE"))]
+        assert len(reports) == 3                      # block sizes 128, 64 and 32
         for report in reports:
             field = lambda name: int(re.search(name + r": (\d+)", report).group(1))
             assert field("VGPRs Spill") == 0 and field("SGPRs Spill") == 0
@@ -91,7 +91,7 @@ def test_hand_scheduled_attention_kernel_compiles_without_spills_or_accumulator_
         lines = open(asm).read().splitlines()
     begins = [i for i, l in enumerate(lines) if "; chunk loop begin" in l]
     ends = [i for i, l in enumerate(lines) if "; chunk loop end" in l]
-    assert len(begins) == 2 and len(ends) == 2
+    assert len(begins) == 3 and len(ends) == 3
     for lo, hi in zip(begins, ends):
         loop = lines[lo:hi]
         assert 144 <= sum("v_mfma_f32_" in l for l in loop) <= 160    # two chunks of 72 slots (+ what drifts in from the drain)

@@ -69,7 +69,7 @@ def _rows(Sb, rng, density, force_last=None):
 
 
 @pytest.mark.parametrize("pairs", ["1", "0"])
-@pytest.mark.parametrize("bs", [128, 64])
+@pytest.mark.parametrize("bs", [128, 64, 32])
 @pytest.mark.parametrize("frames,hg,wg,what", [
     (7, 9, 21, "last key block of 43 keys: a partial first chunk only"),        # N = 1323 = 10 * 128 + 43
     (8, 10, 17, "last key block of 80 (16) keys: one full chunk and a partial one"),  # N = 1360 = 10 * 128 + 80
@@ -109,6 +109,30 @@ def test_ownership_patterns_of_four_rows_at_block_size_64(monkeypatch):
     _check(run, rp, ci)
 
 
+def test_ownership_patterns_of_eight_rows_at_block_size_32(monkeypatch):
+    """Eight query blocks per workgroup, two per wave, a chunk = two entries of the merged list: the four 32 x 32 tiles
+    of a wave's chunk each have their own owner bit.  Rows that list disjoint key blocks (every tile pattern with one
+    owner), one row that lists everything beside seven empty ones, identical rows, an odd number of entries, the
+    partial last key block (11 keys) listed by one query block of a wave only, by both, and by another wave; a last
+    group of one query block."""
+    monkeypatch.setenv("DR_ATTN_PAIRS", "1")
+    run = GpuRun(_case(7, 9, 21, bs=32))
+    Sb = run.wl.Sb                                           # 42: N = 1323 = 41 * 32 + 11; groups of eight: 5 full + 2 blocks
+    assert Sb == 42
+    rows = [[] for _ in range(Sb)]
+    for r in range(8):
+        rows[r] = [r, r + 8, r + 17, 41 - r]                 # disjoint (row 0 lists the partial block): 32 entries
+    rows[8] = list(range(Sb))                                # rows 9..15 empty
+    for r in range(16, 24):
+        rows[r] = [3, 20, 40]                                # identical, odd count
+    rows[24], rows[25], rows[26], rows[27] = [41], [0], [0, 41], [41]       # the partial block: one half of wave 0, both of wave 1
+    rows[28], rows[29], rows[30], rows[31] = [5, 6, 7, 8], [6, 7], [], [4, 5, 6, 7, 8, 9, 41]
+    rows[32], rows[33], rows[34] = [0, 1, 2], [1, 2, 3], [2]                # rows 35..39 empty: waves 2, 3 sit every chunk out
+    rows[40], rows[41] = [0, 1, 41], [40]                    # the last group: two blocks, one wave
+    rp, ci = _csr(rows, Sb)
+    _check(run, rp, ci)
+
+
 def test_ownership_patterns_of_the_merged_list(monkeypatch):
     """Disjoint rows (every chunk skipped by one half of the workgroup), a row that is a strict subset of its
     neighbour, identical rows, and a pair whose merged list starts with a block that only the second row lists (the
@@ -127,10 +151,11 @@ def test_ownership_patterns_of_the_merged_list(monkeypatch):
     _check(run, rp, ci)
 
 
-def test_lists_longer_than_one_register_window_and_per_head_masks(monkeypatch):
+@pytest.mark.parametrize("bs", [128, 32])
+def test_lists_longer_than_one_register_window_and_per_head_masks(bs, monkeypatch):
     """More than 64 key blocks in a merged list (the walk reloads its window), with one mask per head."""
     monkeypatch.setenv("DR_ATTN_PAIRS", "1")
-    wl = _case(10, 30, 32, H=2)                              # N = 9600: 75 key blocks
+    wl = _case(10, 30, 32, H=2, bs=bs)                       # N = 9600: 75 key blocks of 128, 300 of 32
     run = GpuRun(wl)
     Sb = wl.Sb
     rng = np.random.default_rng(9600)
