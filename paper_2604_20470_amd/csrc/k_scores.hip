@@ -93,7 +93,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // contraction chunks of 32 staged through LDS.  The instruction contracts two k per issue (lane halves); a lane
 // reads four consecutive k of its row with one 16-byte LDS load (k = 4 * half + c within a group of eight) and feeds
 // component c to issue c: the k order inside a group is permuted identically for both operands, which a sum does
-// not mind.  WT = 2 (128 x 128 outputs per workgroup) once there are enough tiles to fill the chip, WT = 1 below.
+// not mind.  WT = 2 (128 x 128 outputs per workgroup) for rows of thousands of blocks, WT = 1 below.
 constexpr int kMChunk = 32, kMPad = 36;      // row pitch 144 B keeps the 16-byte reads of 32 rows off the same banks
 
 template <int WT>
@@ -200,7 +200,9 @@ hipError_t launch_scores(const float* pooled, int B, int Hs, int masks, int head
                          float* scores, hipStream_t s) {
     const float scale = 1.0f / (sqrtf((float)d) * (float)heads_per_mask);
     const int t128 = (Sb + 127) / 128, t64 = (Sb + 63) / 64;
-    if ((int64_t)t128 * t128 * B * masks >= 512)
+    // 128 x 128 tiles pay once a row holds thousands of blocks (at 8250 blocks 0.44 against 0.47 ms); below, their
+    // rounding up of Sb and the short contraction loop cost more than they save (591 blocks x 40 heads: 66 against 47 us)
+    if (Sb >= 4096 && (int64_t)t128 * t128 * B * masks >= 512)
         hipLaunchKernelGGL(k_scores_mfma<2>, dim3(t128, t128, B * masks), dim3(256), 0, s, pooled, B, Hs, masks,
                            heads_per_mask, Sb, d, scale, scores);
     else
