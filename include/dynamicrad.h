@@ -234,6 +234,8 @@ dr_status dr_build_mask(dr_ctx* ctx, const dr_shape* shape, int32_t mode, double
  * rows of those 128 queries).  The merged lists live in
  * context-owned device scratch of the size of the colidx arrays the call is given
  * (B * mask_heads * colidx_stride entries), grown on demand: DR_ERR_NOMEM if that allocation fails.
+ * The pre-pass holds one bitmap of Sb bits per merged row in LDS: DR_ERR_UNSUPPORTED when
+ * (256 / Bs) * Sb bits exceed 160 KB (beyond 5 million tokens at block size 32, 84 million at 128).
  * Argument errors (NULL or misaligned pointers, strides, mask_heads) are rejected on the host
  * before any launch; the call itself is asynchronous on `stream`.
  */

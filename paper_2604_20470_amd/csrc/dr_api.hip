@@ -550,6 +550,10 @@ dr_status attn_prepare(dr_ctx* ctx, const dr_shape* shape, const void* Q, const 
     a.bf16 = shape->dtype == DR_BF16;
     if (attn_mfma_small_supported(a) && a.Sb >= (1 << 28))
         return fail(ctx, DR_ERR_UNSUPPORTED, "too many blocks for the packed group lists");
+    // the pre-pass that merges the rows of a workgroup's query blocks keeps one presence bitmap of Sb bits per row in LDS
+    if (a.bf16 && a.td.d == 128 && (size_t)(256 / a.Bs) * (((size_t)a.Sb + 31) / 32) * 4 > 160 * 1024)
+        return fail(ctx, DR_ERR_UNSUPPORTED, "%d key blocks per row: the list-merging pre-pass holds %d bitmaps of that many bits in "
+                    "160 KB of LDS", a.Sb, 256 / a.Bs);
     *out = a;
     return DR_OK;
 }

@@ -541,14 +541,19 @@ hipError_t launch_group_union(int L, const AttnArgs& a, hipStream_t s) {
     if (a.Sb >= (L > 4 ? (1 << 24) : (1 << 28))) return hipErrorInvalidValue;      // the key block must fit below the owner bits
     const int groups = (a.Sb + L - 1) / L;
     const size_t lds = (size_t)L * ((a.Sb + 31) / 32) * 4;
+    if (lds > 160 * 1024) return hipErrorInvalidValue;          // L presence bitmaps of Sb bits each must fit the LDS of a CU
     const dim3 grid(groups, a.mask_heads, a.td.B);
-    if (L == 8)
-        hipLaunchKernelGGL(k_group_union<8>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);
-    else if (L == 4)
-        hipLaunchKernelGGL(k_group_union<4>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);
-    else
-        hipLaunchKernelGGL(k_group_union<2>, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);
-    return hipGetLastError();
+    auto launch = [&](auto kern) -> hipError_t {
+        if (lds > 64 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, a.rowptr, a.colidx, a.colidx_stride, a.Sb, groups, a.gcol, a.gcount);
+        return hipGetLastError();
+    };
+    if (L == 8) return launch(k_group_union<8>);
+    if (L == 4) return launch(k_group_union<4>);
+    return launch(k_group_union<2>);
 }
 
 bool attn_mfma_small_supported(const AttnArgs& a) {
