@@ -565,6 +565,25 @@ def test_maximum_frame_count_and_one_past_it():
         dr.dr_block_scores(run.ctx, shape257, Q, Q, 1, scores257)
 
 
+def test_rows_too_long_for_the_list_merging_pre_pass_are_refused():
+    """The pre-pass that merges the rows of a workgroup's query blocks keeps one bitmap of Sb bits per row in LDS: at
+    block size 32 (eight rows) 164 864 blocks per row are 1 KB too many.  Refused on the host; every buffer has the size
+    the shape would need (empty rows), so that a moved limit shows up as a failed assertion, not as a launch on
+    undersized buffers."""
+    ctx = dr.Context(0)
+    Nf, Hg, Wg = 256, 161, 128
+    N = Nf * Hg * Wg                                                  # 5 275 648 tokens
+    QKV = torch.zeros((1, 1, N, 128), dtype=torch.bfloat16, device="cuda")
+    O = torch.empty_like(QKV)
+    shape = dr.shape_of(QKV, Nf, Hg, Wg, 32)
+    assert shape.Sb == 164864
+    rowptr = torch.zeros((1, 1, shape.Sb + 1), dtype=torch.int32, device="cuda")
+    colidx = torch.zeros((1, 1, 16), dtype=torch.int32, device="cuda")
+    with pytest.raises(dr.DRError, match="UNSUPPORTED.*bitmaps"):
+        dr.dr_sparse_attn_fwd(ctx, shape, QKV, QKV, QKV, rowptr, colidx, 1, 16, O, None)
+    torch.cuda.synchronize()
+
+
 def test_mfma_probe_runs_and_checks_its_arguments():
     ctx = dr.Context(0)
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
